@@ -1,0 +1,19 @@
+"""CPU oracle of the SMILE bi-level MoE layer forward pass (test infrastructure only).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares no code with the HIP library.
+"""
+from .oracle import (  # noqa: F401
+    build,
+    capacity,
+    gate_logits,
+    route,
+    slots_two_stage,
+    dispatch,
+    expert_ffn,
+    combine,
+    aux_loss,
+    layer_forward,
+    threads,
+    RouteResult,
+)
