@@ -1,0 +1,190 @@
+/*
+ * libsmile: forward pass of one SMILE bi-level routed Mixture-of-Experts layer
+ * on one AMD MI355X (gfx950), as a C-ABI library of hand-written HIP kernels.
+ *
+ * Method: "SMILE: Scaling Mixture-of-Experts with Efficient Bi-level Routing",
+ * arXiv 2212.05191.  A token is routed to one of n groups by an inter router
+ * and then to one of the m experts of that group by an intra router
+ * (Section 3.2.1); its output is p_i * q_j * E_{i,j}(x) (Eq. 3); the layer
+ * adds a two-term load-balancing loss (Eq. 4).  On one GPU the paper's node /
+ * GPU hierarchy is a logical two-level grouping: all N = n*m experts are
+ * resident and the two All2All stages become one composed row permutation.
+ *
+ * General rules
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, dense,
+ *     row-major, 16-byte aligned.  The library reads/writes it only during the
+ *     call's enqueued work and never frees or keeps it.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued asynchronously on it; no call synchronises, and no
+ *     call other than smile_create/smile_destroy allocates or frees memory.
+ *   - Every function returns a smile_status; nothing throws or aborts.
+ *     Argument checks happen on the host before anything is enqueued, so a
+ *     non-OK status means no work was submitted (except SMILE_HIP_ERROR from a
+ *     failed launch).
+ *   - Notation: T tokens, d = d_model, F = d_ff, n = n_groups, m = m_local,
+ *     N = n*m, flat expert id e = group*m + local, C = capacity (rows of each
+ *     expert's buffer).  dtype is the storage type of x, router and expert
+ *     weights, the expert buffers and y: 0 = fp32, 1 = bfloat16.  Logits,
+ *     probabilities, gates and the loss are always fp32.
+ *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for bf16:
+ *     d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096,
+ *     n + m <= 128 for smile_gate_logits; N*C*max(d,F) < 2^40 elements;
+ *     N*C and T below 2^31.
+ *   - Floating-point inputs must be finite; NaN/Inf give unspecified results.
+ */
+#ifndef SMILE_H
+#define SMILE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum smile_status {
+    SMILE_OK = 0,
+    SMILE_INVALID_ARG = 1,   /* NULL or misaligned pointer, NULL ctx/desc */
+    SMILE_BAD_SHAPE = 2,     /* a size is out of range or violates a divisibility rule */
+    SMILE_UNSUPPORTED = 3,   /* unknown dtype / activation, or a shape no kernel covers */
+    SMILE_WORKSPACE = 4,     /* caller-supplied workspace too small or misaligned */
+    SMILE_HIP_ERROR = 5      /* a HIP runtime call failed (allocation, launch) */
+} smile_status;
+
+enum { SMILE_DTYPE_F32 = 0, SMILE_DTYPE_BF16 = 1 };
+enum { SMILE_ACT_RELU = 0, SMILE_ACT_GELU = 1 };   /* GELU is the exact erf form (Section 4.1) */
+
+/* Static description of one layer; copied by smile_create. */
+typedef struct smile_layer_desc {
+    int32_t T;          /* tokens per call */
+    int32_t d_model;
+    int32_t d_ff;
+    int32_t n_groups;   /* n: fan-out of the inter router (the paper's nodes) */
+    int32_t m_local;    /* m: fan-out of the intra router (the paper's GPUs per node) */
+    int32_t capacity;   /* C: rows per expert buffer, see smile_capacity */
+    int32_t dtype;      /* SMILE_DTYPE_* */
+    int32_t act;        /* SMILE_ACT_* */
+    float alpha;        /* Eq. 4 coefficients */
+    float beta;
+} smile_layer_desc;
+
+typedef struct smile_ctx smile_ctx;   /* opaque: a validated desc + device workspace */
+
+/* Static string for a status code (never NULL). */
+const char *smile_status_string(int32_t status);
+
+/* Library version, e.g. "0.1.0". */
+const char *smile_version(void);
+
+/* Switch-style expert capacity for the "capacity factor" of Section 4.2:
+ * ceil(cf * T / N), at least 1.  Host helper; returns -1 on invalid input. */
+int32_t smile_capacity(int32_t T, int32_t N, double capacity_factor);
+
+/* Host-only check of a desc against the limits above (no GPU needed). */
+smile_status smile_validate_desc(const smile_layer_desc *desc);
+
+/* Bytes of device workspace a ctx for `desc` needs (routing histograms and
+ * partial sums, and the hidden activation h[N,C,F] between the two expert
+ * GEMMs).  Host-only. */
+smile_status smile_workspace_bytes(const smile_layer_desc *desc, size_t *bytes);
+
+/* Create a ctx whose workspace the library allocates with hipMalloc on the
+ * current device (freed by smile_destroy). */
+smile_status smile_create(const smile_layer_desc *desc, smile_ctx **ctx);
+
+/* Create a ctx on caller-owned device memory: `workspace` must be 256-byte
+ * aligned, at least smile_workspace_bytes() long and must outlive the ctx.
+ * Nothing is allocated on the device.  Calls on one ctx must not overlap. */
+smile_status smile_create_with_workspace(const smile_layer_desc *desc, void *workspace, size_t bytes,
+                                         smile_ctx **ctx);
+
+/* Release a ctx (and its workspace if the library allocated it).  The caller
+ * must have synchronised every stream that used it.  NULL is allowed. */
+smile_status smile_destroy(smile_ctx *ctx);
+
+/* Step 1 -- router logits r(x) = W_r x (Section 2, text before Eq. 1) for the
+ * two tied routers of Section 3.2.1, both reading the same token vector:
+ *   logits_inter[t,i] = sum_k x[t,k] * w_inter[i,k]      [T,n] fp32
+ *   logits_intra[t,j] = sum_k x[t,k] * w_intra[j,k]      [T,m] fp32
+ * x[T,d], w_inter[n,d], w_intra[m,d] in the ctx dtype; products accumulate in fp32. */
+smile_status smile_gate_logits(smile_ctx *ctx, const void *x, const void *w_inter, const void *w_intra,
+                               float *logits_inter, float *logits_intra, void *stream);
+
+/* Steps 2-3 -- bi-level top-1 routing with capacity (Section 3.2.1; Eq. 1
+ * read as a softmax; Section 3.2.2 for the statistics; Section 4.2 capacity).
+ *   a[t,:] = logits_inter[t,:] + bias_inter            (one fp32 add, bias may be NULL)
+ *   group_idx[t] = lowest index of max a[t,:];  p = softmax(a[t,:]);  p_top[t] = p[group_idx[t]]
+ *   c[t,:] = logits_intra[t,:] + bias_intra[group_idx[t],:]   (bias_intra[n,m] may be NULL)
+ *   local_idx[t] = lowest index of max c[t,:];  q = softmax(c[t,:]);  q_top[t] = q[local_idx[t]]
+ *   gate[t] = p_top[t] * q_top[t]                      (Eq. 3)
+ *   pos_in_group[t] = number of earlier tokens with the same group       (stage-1 position)
+ *   rank = number of earlier tokens with the same (group, local)          (stage-2 position)
+ *   slot[t] = rank if rank < C, else -1 (token dropped)
+ *   group_count[n], local_count[m] (summed over all groups), expert_count[N]: top-1 counts of all T
+ *   tokens, before drops;  kept_count[e] = min(expert_count[e], C);
+ *   p_sum[i] = sum_t p[t,i];  q_sum[j] = sum_t q[t,j]    (fp32)
+ * Integer outputs are exact and independent of launch geometry; float sums are
+ * accumulated in a fixed order, so repeated calls give identical bits. */
+smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, const float *logits_intra,
+                                 const float *bias_inter, const float *bias_intra,
+                                 int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot,
+                                 float *gate, float *p_top, float *q_top,
+                                 int32_t *group_count, int32_t *local_count, int32_t *expert_count,
+                                 int32_t *kept_count, float *p_sum, float *q_sum, void *stream);
+
+/* Step 3 -- dispatch: xe[e, slot[t], :] = x[t, :] for every kept token, e =
+ * group_idx[t]*m + local_idx[t] (the two routing hops of Section 3.2.1 composed
+ * into one row move).  xe[N,C,d] in the ctx dtype; rows at or beyond
+ * kept_count[e] are not written. */
+smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_idx, const int32_t *local_idx,
+                            const int32_t *slot, void *xe, void *stream);
+
+/* Step 3 -- expert FFN E_e of Eq. 3 (Section 4.1: hidden -> intermediate ->
+ * hidden with the activation of the ctx) on rows r < kept_count[e]:
+ *   h  = act(xe[e,r,:] . w1[e]^T + b1[e])     w1[N,F,d]  (out-features x in-features), b1[N,F] or NULL
+ *   ye[e,r,:] = h . w2[e]^T + b2[e]           w2[N,d,F],                              b2[N,d] or NULL
+ * Weights and biases in the ctx dtype; accumulation in fp32; h is rounded to
+ * the ctx dtype between the two products.  kept_count is read on the device
+ * (no host sync); rows at or beyond kept_count[e] of ye are not written. */
+smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                              const void *w1, const void *b1, const void *w2, const void *b2,
+                              void *ye, void *stream);
+
+/* Step 4 -- combine (Eq. 3): y[t,:] = gate[t] * ye[e, slot[t], :] for kept
+ * tokens, 0 for dropped ones; product in fp32, rounded once to the ctx dtype. */
+smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,
+                           const int32_t *slot, const float *gate, void *y, void *stream);
+
+/* Step 4 -- additive load-balancing loss (Eq. 4), from the statistics of
+ * smile_route_bilevel:
+ *   out3[0] = n * sum_i (group_count[i]/T) * (p_sum[i]/T)
+ *   out3[1] = m * sum_j (local_count[j]/T) * (q_sum[j]/T)
+ *   out3[2] = alpha*out3[0] + beta*out3[1]
+ * out3: 3 fp32 values on the device. */
+smile_status smile_aux_loss(smile_ctx *ctx, const int32_t *group_count, const int32_t *local_count,
+                            const float *p_sum, const float *q_sum, float *out3, void *stream);
+
+/* All tensors of one forward pass, for smile_layer_forward. */
+typedef struct smile_layer_io {
+    /* inputs */
+    const void *x, *w_inter, *w_intra, *w1, *b1, *w2, *b2;
+    const float *bias_inter, *bias_intra;
+    /* intermediates and outputs (all caller-allocated) */
+    float *logits_inter, *logits_intra;
+    int32_t *group_idx, *local_idx, *pos_in_group, *slot;
+    float *gate, *p_top, *q_top;
+    int32_t *group_count, *local_count, *expert_count, *kept_count;
+    float *p_sum, *q_sum;
+    void *xe, *ye, *y;
+    float *loss3;
+} smile_layer_io;
+
+/* Convenience: enqueue the six steps above in order on `stream`
+ * (gate logits, route, dispatch, expert FFN, combine, loss).  Same checks,
+ * same results as calling them one by one. */
+smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMILE_H */

@@ -1,0 +1,46 @@
+// Additive load-balancing loss (Eq. 4): inter = n * sum_i f_i P_i, intra = m * sum_j f_j Q_j with
+// f = count / T and P, Q = probability sum / T; total = alpha*inter + beta*intra.  n + m values:
+// one wave, each lane sums its strided share serially, then a fixed butterfly across lanes.
+#include "smile_internal.hpp"
+
+namespace smile {
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(64) void aux_loss_kernel(
+    const int32_t *__restrict__ group_count, const int32_t *__restrict__ local_count,
+    const float *__restrict__ p_sum, const float *__restrict__ q_sum, int T, int n, int m,
+    float alpha, float beta, float *__restrict__ out3)
+{
+    const int lane = threadIdx.x;
+    const float inv_t = 1.0f / (float)T;
+    float a = 0.f, b = 0.f;
+    for (int i = lane; i < n; i += 64) a += ((float)group_count[i] * inv_t) * (p_sum[i] * inv_t);
+    for (int j = lane; j < m; j += 64) b += ((float)local_count[j] * inv_t) * (q_sum[j] * inv_t);
+    a = wave_sum(a) * (float)n;
+    b = wave_sum(b) * (float)m;
+    if (lane == 0) {
+        out3[0] = a;
+        out3[1] = b;
+        out3[2] = alpha * a + beta * b;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
+                           const float *p_sum, const float *q_sum, float *out3, hipStream_t s)
+{
+    hipLaunchKernelGGL(aux_loss_kernel, dim3(1), dim3(64), 0, s, group_count, local_count, p_sum, q_sum, d.T,
+                       d.n_groups, d.m_local, d.alpha, d.beta, out3);
+    return hipGetLastError();
+}
+
+}  // namespace smile

@@ -1,0 +1,148 @@
+// Router logits r(x) = W_r x (Section 2, text before Eq. 1) for the inter router W_p[n,d] and the
+// intra router W_q[m,d] (Section 3.2.1: two tied routers reading the same token), computed as one
+// skinny product [T,d] x [d,n+m].  n+m is 10-40 in the paper-shaped workloads, so the kernel is
+// bound by the single read of x from HBM; the weights (<= 80 KB) stay in L2.
+//
+// bf16: one workgroup of 4 waves owns 16 token rows; the waves split the K (d) range in 64-wide
+// chunks, each feeding v_mfma_f32_16x16x32_bf16 straight from global memory (a lane reads 32
+// contiguous bytes of its row, so 4 lanes cover a full 128-byte line), then the 4 partial
+// accumulators are summed through LDS in a fixed order.  16 rows per workgroup keeps >= 512
+// workgroups in flight for the smallest paper-shaped batch (T = 8192).
+// fp32: plain FMA kernel, one thread per (token, column), 4 partial sums.
+#include "smile_internal.hpp"
+
+namespace smile {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int kRows = 16;      // token rows per workgroup
+constexpr int kWaves = 4;      // K-split factor
+
+// CT = number of 16-column tiles covering the n+m logits columns.
+template <int CT>
+__global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
+    const __bf16 *__restrict__ x, const __bf16 *__restrict__ w_inter, const __bf16 *__restrict__ w_intra,
+    float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m)
+{
+    __shared__ f32x4 red[kWaves - 1][CT][64];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, kg = lane >> 4;
+    const int row0 = blockIdx.x * kRows;
+    const __bf16 *xrow = x + (size_t)min(row0 + r, T - 1) * d;
+
+    // the weight row this lane feeds as the B operand of column tile ct (null: padding column)
+    const __bf16 *wrow[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int c = ct * 16 + r;
+        wrow[ct] = c < n ? w_inter + (size_t)c * d : (c < n + m ? w_intra + (size_t)(c - n) * d : nullptr);
+    }
+
+    f32x4 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int chunks = d / 64;
+    const int iters = (chunks - wave + kWaves - 1) / kWaves;   // this wave's chunks: wave, wave + 4, ...
+    for (int it = 0; it < iters; ++it) {
+        // the contraction index may be visited in any order as long as A and B agree: lane group kg
+        // takes k0 + kg*16 + [0,8) for the first MFMA and + [8,16) for the second
+        const int k = (wave + it * kWaves) * 64 + kg * 16;
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(xrow + k);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(xrow + k + 8);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const bf16x8 b0 = wrow[ct] ? *reinterpret_cast<const bf16x8 *>(wrow[ct] + k) : zero;
+            const bf16x8 b1 = wrow[ct] ? *reinterpret_cast<const bf16x8 *>(wrow[ct] + k + 8) : zero;
+            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0, acc[ct], 0, 0, 0);
+            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, acc[ct], 0, 0, 0);
+        }
+    }
+
+    if (wave > 0) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) red[wave - 1][ct][lane] = acc[ct];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            f32x4 s = acc[ct];
+#pragma unroll
+            for (int w = 0; w < kWaves - 1; ++w) s += red[w][ct][lane];
+            // accumulator element i of this lane is (row kg*4 + i, column r) of the 16x16 tile
+            const int c = ct * 16 + r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = row0 + kg * 4 + i;
+                if (row < T) {
+                    if (c < n) logits_inter[(size_t)row * n + c] = s[i];
+                    else if (c < n + m) logits_intra[(size_t)row * m + (c - n)] = s[i];
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void gate_logits_f32_kernel(
+    const float *__restrict__ x, const float *__restrict__ w_inter, const float *__restrict__ w_intra,
+    float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m)
+{
+    const long long id = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int cols = n + m;
+    if (id >= (long long)T * cols) return;
+    const int t = (int)(id / cols), c = (int)(id - (long long)t * cols);
+    const f32x4 *xr = reinterpret_cast<const f32x4 *>(x + (size_t)t * d);
+    const f32x4 *wr = reinterpret_cast<const f32x4 *>(c < n ? w_inter + (size_t)c * d : w_intra + (size_t)(c - n) * d);
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < d / 4; ++k) s += xr[k] * wr[k];
+    const float v = (s[0] + s[1]) + (s[2] + s[3]);
+    if (c < n) logits_inter[(size_t)t * n + c] = v;
+    else logits_intra[(size_t)t * m + (c - n)] = v;
+}
+
+template <int CT>
+void launch_bf16(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+                 float *logits_inter, float *logits_intra, hipStream_t s)
+{
+    const int blocks = (d.T + kRows - 1) / kRows;
+    hipLaunchKernelGGL(gate_logits_bf16_kernel<CT>, dim3(blocks), dim3(64 * kWaves), 0, s,
+                       static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
+                       static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
+                       d.n_groups, d.m_local);
+}
+
+}  // namespace
+
+hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+                              float *logits_inter, float *logits_intra, hipStream_t s)
+{
+    const int cols = d.n_groups + d.m_local;
+    if (d.dtype == SMILE_DTYPE_BF16) {
+        switch ((cols + 15) / 16) {
+        case 1: launch_bf16<1>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 2: launch_bf16<2>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 3: launch_bf16<3>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 4: launch_bf16<4>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 5: launch_bf16<5>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 6: launch_bf16<6>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 7: launch_bf16<7>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        case 8: launch_bf16<8>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
+        default: return hipErrorInvalidValue;
+        }
+    } else {
+        const long long total = (long long)d.T * cols;
+        hipLaunchKernelGGL(gate_logits_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           static_cast<const float *>(x), static_cast<const float *>(w_inter),
+                           static_cast<const float *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
+                           d.n_groups, d.m_local);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace smile

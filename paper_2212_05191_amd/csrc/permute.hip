@@ -1,0 +1,142 @@
+// Dispatch and combine: the token <-> expert-buffer row permutation (Section 3.2.1; on one GPU the
+// paper's inter- and intra-node hops are composed into a single row move) and the gate-weighted
+// return (Eq. 3).  Both are pure HBM streaming: a row is d*elem bytes (1.5-2 KiB for the bf16
+// configurations), moved as 16-byte pieces with consecutive lanes on consecutive pieces, so every
+// wave access is a run of full cache lines.  Each thread moves kPieces pieces spaced one grid-width
+// apart so that several loads are in flight per lane.
+#include "smile_internal.hpp"
+
+namespace smile {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPieces = 4;
+
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+// xe[(g*m+l)*C + slot] <- x[t] for kept tokens.  ppr = 16-byte pieces per row.
+__global__ __launch_bounds__(kThreads) void dispatch_kernel(
+    const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ slot, u32x4 *__restrict__ xe, long long total, int ppr, int m, int C)
+{
+    const long long stride = (long long)gridDim.x * kThreads;
+    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
+    u32x4 v[kPieces];
+    long long dst[kPieces];
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+        const long long p = id + i * stride;
+        dst[i] = -1;
+        if (p < total) {
+            const int t = (int)(p / ppr);
+            const int c = (int)(p - (long long)t * ppr);
+            const int sl = slot[t];
+            if (sl >= 0) {
+                dst[i] = ((long long)(group_idx[t] * m + local_idx[t]) * C + sl) * ppr + c;
+                v[i] = x[p];
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i)
+        if (dst[i] >= 0) xe[dst[i]] = v[i];
+}
+
+template <bool kBf16>
+__device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
+{
+    u32x4 r;
+    if constexpr (kBf16) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            // a bf16 is the upper half of an fp32
+            const float lo = __uint_as_float(v[k] << 16) * gt;
+            const float hi = __uint_as_float(v[k] & 0xffff0000u) * gt;
+            bf16x2 pk;
+            pk[0] = (__bf16)lo;   // round to nearest even
+            pk[1] = (__bf16)hi;
+            r[k] = __builtin_bit_cast(uint32_t, pk);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = __float_as_uint(__uint_as_float(v[k]) * gt);
+    }
+    return r;
+}
+
+// y[t] <- gate[t] * ye[(g*m+l)*C + slot] for kept tokens, 0 for dropped ones.
+template <bool kBf16>
+__global__ __launch_bounds__(kThreads) void combine_kernel(
+    const u32x4 *__restrict__ ye, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ slot, const float *__restrict__ gate, u32x4 *__restrict__ y,
+    long long total, int ppr, int m, int C)
+{
+    const long long stride = (long long)gridDim.x * kThreads;
+    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
+    u32x4 v[kPieces];
+    float gt[kPieces];
+    bool kept[kPieces];
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+        const long long p = id + i * stride;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        gt[i] = 0.f;
+        kept[i] = false;
+        if (p < total) {
+            const int t = (int)(p / ppr);
+            const int c = (int)(p - (long long)t * ppr);
+            const int sl = slot[t];
+            if (sl >= 0) {
+                v[i] = ye[((long long)(group_idx[t] * m + local_idx[t]) * C + sl) * ppr + c];
+                gt[i] = gate[t];
+                kept[i] = true;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+        const long long p = id + i * stride;
+        if (p < total) y[p] = kept[i] ? scale_piece<kBf16>(v[i], gt[i]) : u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+int grid_for(long long total)
+{
+    const long long per_block = (long long)kThreads * kPieces;
+    return (int)((total + per_block - 1) / per_block);
+}
+
+}  // namespace
+
+hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
+                           const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s)
+{
+    const int esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
+    const int ppr = d.d_model * esz / 16;
+    const long long total = (long long)d.T * ppr;
+    hipLaunchKernelGGL(dispatch_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
+                       static_cast<const u32x4 *>(x), group_idx, local_idx, slot, static_cast<u32x4 *>(xe), total,
+                       ppr, d.m_local, d.capacity);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
+                          const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s)
+{
+    const bool bf = d.dtype == SMILE_DTYPE_BF16;
+    const int ppr = d.d_model * (bf ? 2 : 4) / 16;
+    const long long total = (long long)d.T * ppr;
+    const dim3 grid(grid_for(total)), block(kThreads);
+    if (bf)
+        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, static_cast<const u32x4 *>(ye), group_idx,
+                           local_idx, slot, gate, static_cast<u32x4 *>(y), total, ppr, d.m_local, d.capacity);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, static_cast<const u32x4 *>(ye), group_idx,
+                           local_idx, slot, gate, static_cast<u32x4 *>(y), total, ppr, d.m_local, d.capacity);
+    return hipGetLastError();
+}
+
+}  // namespace smile

@@ -1,0 +1,260 @@
+// Bi-level top-1 routing with per-expert capacity (Section 3.2.1, Section 3.2.2 statistics,
+// Section 4.2 capacity), as three small kernels:
+//
+//   route_decide   one thread per token: biased logits -> top-1 group and local expert, the two
+//                  softmax probabilities (Eq. 1 read as a softmax), the gate p*q (Eq. 3); per-block
+//                  column sums of p and q; the token's rank among EARLIER tokens of the same block
+//                  with the same group / the same expert (wave64 ballots + LDS counters); per-block
+//                  histograms.
+//   route_scan     one workgroup: exclusive scan of the block histograms along the block axis (turning
+//                  them into block offsets), totals, kept counts, and the fixed-order sums of p and q.
+//   route_finalize one thread per token: global rank = block offset + in-block rank; capacity cut.
+//
+// Everything that decides an integer is integer arithmetic or an fp32 compare of the caller's logits,
+// so the result depends only on the logits and the token order, never on the launch geometry.  No
+// atomics order, no inter-workgroup waiting, no memory that must be cleared beforehand.
+#include "smile_internal.hpp"
+
+namespace smile {
+
+namespace {
+
+constexpr int kColChunk = 32;   // probability columns summed per LDS pass
+
+__device__ __forceinline__ unsigned long long lanemask_lt()
+{
+    const unsigned lane = __lane_id();
+    return lane == 0 ? 0ull : (~0ull >> (64 - lane));
+}
+
+// Lanes of this wave (among `valid` ones) holding the same key; key < 2^bits.
+__device__ __forceinline__ unsigned long long match_any(int key, int bits, bool valid)
+{
+    unsigned long long mask = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+        const bool set = (key >> b) & 1;
+        const unsigned long long bal = __ballot(valid && set);
+        mask &= set ? bal : ~bal;
+    }
+    return mask;
+}
+
+// Top-1 over `len` biased logits: lowest index of the maximum, and 1/sum(exp(a - max)) which is
+// the softmax probability of that maximum.  `row` and `bias` (may be null) are read twice.
+__device__ __forceinline__ void top1_softmax(const float *__restrict__ row, const float *__restrict__ bias,
+                                             int len, int &arg, float &mx, float &inv_z)
+{
+    arg = 0;
+    mx = bias ? __fadd_rn(row[0], bias[0]) : row[0];
+    for (int i = 1; i < len; ++i) {
+        const float a = bias ? __fadd_rn(row[i], bias[i]) : row[i];
+        if (a > mx) { mx = a; arg = i; }
+    }
+    float z = 0.f;
+    for (int i = 0; i < len; ++i) {
+        const float a = bias ? __fadd_rn(row[i], bias[i]) : row[i];
+        z += expf(a - mx);
+    }
+    inv_z = 1.0f / z;
+}
+
+// Column sums over the block's tokens of prob[t, c] = exp(a[t,c] - mx_t) * inv_z_t, written to
+// out[c], in a fixed order: 8 segments of 32 tokens summed serially, then the 8 partials serially.
+__device__ __forceinline__ void block_column_sums(const float *__restrict__ row, const float *__restrict__ bias,
+                                                  int len, float mx, float inv_z, bool valid,
+                                                  float (*tile)[kColChunk + 1], float (*part)[kColChunk],
+                                                  float *__restrict__ out)
+{
+    const int tid = threadIdx.x;
+    for (int c0 = 0; c0 < len; c0 += kColChunk) {
+        const int w = min(kColChunk, len - c0);
+        for (int i = 0; i < w; ++i) {
+            float p = 0.f;
+            if (valid) {
+                const float a = bias ? __fadd_rn(row[c0 + i], bias[c0 + i]) : row[c0 + i];
+                p = expf(a - mx) * inv_z;
+            }
+            tile[tid][i] = p;
+        }
+        __syncthreads();
+        const int col = tid & (kColChunk - 1), seg = tid / kColChunk;   // 8 segments of 32 tokens
+        if (col < w) {
+            float s = 0.f;
+            for (int j = 0; j < kRouteBlock / 8; ++j) s += tile[seg * (kRouteBlock / 8) + j][col];
+            part[seg][col] = s;
+        }
+        __syncthreads();
+        if (tid < w) {
+            float s = 0.f;
+            for (int sg = 0; sg < 8; ++sg) s += part[sg][tid];
+            out[c0 + tid] = s;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
+    const float *__restrict__ logits_inter, const float *__restrict__ logits_intra,
+    const float *__restrict__ bias_inter, const float *__restrict__ bias_intra,
+    int T, int n, int m, int bits_n, int bits_N,
+    int32_t *__restrict__ group_idx, int32_t *__restrict__ local_idx,
+    int32_t *__restrict__ pos_in_block, int32_t *__restrict__ rank_in_block,
+    float *__restrict__ gate, float *__restrict__ p_top, float *__restrict__ q_top,
+    int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ block_group_hist,
+    float *__restrict__ block_p_sum, float *__restrict__ block_q_sum)
+{
+    extern __shared__ int32_t hist[];                  // [N] expert counters, then [n] group counters
+    __shared__ float tile[kRouteBlock][kColChunk + 1];
+    __shared__ float part[8][kColChunk];
+
+    const int N = n * m;
+    int32_t *ghist = hist + N;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int t = b * kRouteBlock + tid;
+    const bool valid = t < T;
+
+    for (int i = tid; i < N + n; i += kRouteBlock) hist[i] = 0;
+
+    int g = 0, l = 0;
+    float mx_p = 0.f, iz_p = 0.f, mx_q = 0.f, iz_q = 0.f;
+    const float *rp = logits_inter + (size_t)(valid ? t : 0) * n;
+    const float *rq = logits_intra + (size_t)(valid ? t : 0) * m;
+    const float *bq = nullptr;
+    if (valid) {
+        top1_softmax(rp, bias_inter, n, g, mx_p, iz_p);
+        bq = bias_intra ? bias_intra + (size_t)g * m : nullptr;
+        top1_softmax(rq, bq, m, l, mx_q, iz_q);
+        group_idx[t] = g;
+        local_idx[t] = l;
+        p_top[t] = iz_p;
+        q_top[t] = iz_q;
+        gate[t] = iz_p * iz_q;
+    }
+    __syncthreads();   // counters are zero
+
+    // rank among earlier tokens of this block: the waves take turns in token order
+    const int e = g * m + l;
+    const unsigned long long me = match_any(e, bits_N, valid);
+    const unsigned long long mg = match_any(g, bits_n, valid);
+    const unsigned long long lt = lanemask_lt();
+    const int lane = __lane_id();
+    const int wave = tid >> 6;
+    for (int w = 0; w < kRouteBlock / 64; ++w) {
+        if (wave == w && valid) {
+            const int base_e = hist[e];
+            const int base_g = ghist[g];
+            rank_in_block[t] = base_e + __popcll(me & lt);
+            pos_in_block[t] = base_g + __popcll(mg & lt);
+            // the last lane of each matching set publishes the new count
+            if (63 - __clzll(me) == lane) hist[e] = base_e + __popcll(me);
+            if (63 - __clzll(mg) == lane) ghist[g] = base_g + __popcll(mg);
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < N; i += kRouteBlock) block_expert_hist[(size_t)b * N + i] = hist[i];
+    for (int i = tid; i < n; i += kRouteBlock) block_group_hist[(size_t)b * n + i] = ghist[i];
+
+    block_column_sums(rp, bias_inter, n, mx_p, iz_p, valid, tile, part, block_p_sum + (size_t)b * n);
+    block_column_sums(rq, bq, m, mx_q, iz_q, valid, tile, part, block_q_sum + (size_t)b * m);
+}
+
+__global__ __launch_bounds__(1024) void route_scan_kernel(
+    int B, int n, int m, int C,
+    int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ block_group_hist,
+    const float *__restrict__ block_p_sum, const float *__restrict__ block_q_sum,
+    int32_t *__restrict__ group_count, int32_t *__restrict__ local_count,
+    int32_t *__restrict__ expert_count, int32_t *__restrict__ kept_count,
+    float *__restrict__ p_sum, float *__restrict__ q_sum)
+{
+    extern __shared__ int32_t ecnt[];   // [N]
+    const int N = n * m;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int e = tid; e < N; e += nt) {
+        int run = 0;
+        for (int b = 0; b < B; ++b) {
+            const int v = block_expert_hist[(size_t)b * N + e];
+            block_expert_hist[(size_t)b * N + e] = run;
+            run += v;
+        }
+        ecnt[e] = run;
+        expert_count[e] = run;
+        kept_count[e] = min(run, C);
+    }
+    // groups, and the probability sums, go to the threads from the top so they overlap the experts
+    for (int i = nt - 1 - tid; i < n; i += nt) {
+        int run = 0;
+        for (int b = 0; b < B; ++b) {
+            const int v = block_group_hist[(size_t)b * n + i];
+            block_group_hist[(size_t)b * n + i] = run;
+            run += v;
+        }
+        group_count[i] = run;
+        float s = 0.f;
+        for (int b = 0; b < B; ++b) s += block_p_sum[(size_t)b * n + i];
+        p_sum[i] = s;
+    }
+    for (int j = nt - 1 - tid; j < m; j += nt) {
+        float s = 0.f;
+        for (int b = 0; b < B; ++b) s += block_q_sum[(size_t)b * m + j];
+        q_sum[j] = s;
+    }
+    __syncthreads();
+    for (int j = tid; j < m; j += nt) {
+        int s = 0;
+        for (int i = 0; i < n; ++i) s += ecnt[i * m + j];
+        local_count[j] = s;
+    }
+}
+
+__global__ __launch_bounds__(kRouteBlock) void route_finalize_kernel(
+    int T, int n, int m, int C,
+    const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
+    int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot)
+{
+    const int b = blockIdx.x;
+    const int t = b * kRouteBlock + threadIdx.x;
+    if (t >= T) return;
+    const int g = group_idx[t], l = local_idx[t];
+    const int N = n * m;
+    const int rank = block_expert_off[(size_t)b * N + g * m + l] + slot[t];
+    slot[t] = rank < C ? rank : -1;
+    pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_group[t];
+}
+
+int ceil_log2(int v)
+{
+    int b = 0;
+    while ((1 << b) < v) ++b;
+    return b;
+}
+
+}  // namespace
+
+hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const float *logits_inter,
+                        const float *logits_intra, const float *bias_inter, const float *bias_intra,
+                        int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
+                        float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
+                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s)
+{
+    const int n = d.n_groups, m = d.m_local, N = n * m;
+    const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
+    const size_t lds1 = sizeof(int32_t) * (size_t)(N + n);
+    hipLaunchKernelGGL(route_decide_kernel, dim3(B), dim3(kRouteBlock), lds1, s, logits_inter, logits_intra,
+                       bias_inter, bias_intra, d.T, n, m, ceil_log2(n), ceil_log2(N), group_idx, local_idx,
+                       pos_in_group, slot, gate, p_top, q_top, ws.block_expert_hist, ws.block_group_hist,
+                       ws.block_p_sum, ws.block_q_sum);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), sizeof(int32_t) * (size_t)N, s, B, n, m,
+                       d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
+                       group_count, local_count, expert_count, kept_count, p_sum, q_sum);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,
+                       local_idx, ws.block_expert_hist, ws.block_group_hist, pos_in_group, slot);
+    return hipGetLastError();
+}
+
+}  // namespace smile

@@ -1,0 +1,249 @@
+// C-ABI entry points of libsmile: argument validation, ctx / workspace management and
+// dispatch to the kernel launchers.  All checks run on the host before anything is enqueued.
+#include <cmath>
+#include <cstdlib>
+#include <new>
+
+#include "smile_internal.hpp"
+
+namespace smile {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+Layout workspace_layout(const smile_layer_desc &d)
+{
+    Layout L{};
+    const size_t B = ((size_t)d.T + kRouteBlock - 1) / kRouteBlock;
+    const size_t N = (size_t)d.n_groups * d.m_local;
+    const size_t esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
+    size_t off = 0;
+    L.route_blocks = (int32_t)B;
+    L.off_block_expert_hist = off; off = align_up(off + B * N * sizeof(int32_t), 256);
+    L.off_block_group_hist = off;  off = align_up(off + B * d.n_groups * sizeof(int32_t), 256);
+    L.off_block_p_sum = off;       off = align_up(off + B * d.n_groups * sizeof(float), 256);
+    L.off_block_q_sum = off;       off = align_up(off + B * d.m_local * sizeof(float), 256);
+    L.off_hidden = off;            off = align_up(off + N * (size_t)d.capacity * d.d_ff * esz, 256);
+    L.total = off;
+    return L;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// required pointer: non-NULL and 16-byte aligned
+static bool bad(const void *p) { return p == nullptr || !aligned16(p); }
+// optional pointer: NULL or 16-byte aligned
+static bool bad_opt(const void *p) { return p != nullptr && !aligned16(p); }
+
+static smile_status from_hip(hipError_t e)
+{
+    if (e == hipSuccess) return SMILE_OK;
+    (void)hipGetLastError();   // do not leave a sticky launch error behind for the caller's next call
+    return SMILE_HIP_ERROR;
+}
+
+}  // namespace smile
+
+using namespace smile;
+
+extern "C" {
+
+const char *smile_status_string(int32_t status)
+{
+    switch (status) {
+    case SMILE_OK: return "ok";
+    case SMILE_INVALID_ARG: return "invalid argument (NULL or misaligned pointer)";
+    case SMILE_BAD_SHAPE: return "bad shape (size out of range or not divisible as required)";
+    case SMILE_UNSUPPORTED: return "unsupported dtype, activation or shape";
+    case SMILE_WORKSPACE: return "workspace too small or misaligned";
+    case SMILE_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *smile_version(void) { return "0.1.0"; }
+
+int32_t smile_capacity(int32_t T, int32_t N, double capacity_factor)
+{
+    if (T < 1 || N < 1 || !(capacity_factor > 0.0) || !std::isfinite(capacity_factor)) return -1;
+    double c = std::ceil(capacity_factor * (double)T / (double)N);
+    if (c < 1.0) c = 1.0;
+    if (c > 2147483647.0) return -1;
+    return (int32_t)c;
+}
+
+smile_status smile_validate_desc(const smile_layer_desc *desc)
+{
+    if (!desc) return SMILE_INVALID_ARG;
+    const smile_layer_desc &d = *desc;
+    if (d.dtype != SMILE_DTYPE_F32 && d.dtype != SMILE_DTYPE_BF16) return SMILE_UNSUPPORTED;
+    if (d.act != SMILE_ACT_RELU && d.act != SMILE_ACT_GELU) return SMILE_UNSUPPORTED;
+    if (d.T < 1 || d.d_model < 1 || d.d_ff < 1 || d.n_groups < 1 || d.m_local < 1 || d.capacity < 1)
+        return SMILE_BAD_SHAPE;
+    if (d.n_groups > 1024 || d.m_local > 1024) return SMILE_BAD_SHAPE;
+    const int64_t N = (int64_t)d.n_groups * d.m_local;
+    if (N > 4096) return SMILE_BAD_SHAPE;
+    if (d.d_model % 8 || d.d_ff % 8) return SMILE_BAD_SHAPE;
+    if (d.dtype == SMILE_DTYPE_BF16 && (d.d_model % 64 || d.d_ff % 64)) return SMILE_BAD_SHAPE;
+    if (N * d.capacity >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
+    const int64_t widest = d.d_model > d.d_ff ? d.d_model : d.d_ff;
+    if ((double)N * d.capacity * (double)widest >= 1099511627776.0) return SMILE_BAD_SHAPE;
+    if (!std::isfinite(d.alpha) || !std::isfinite(d.beta)) return SMILE_BAD_SHAPE;
+    return SMILE_OK;
+}
+
+smile_status smile_workspace_bytes(const smile_layer_desc *desc, size_t *bytes)
+{
+    if (!bytes) return SMILE_INVALID_ARG;
+    smile_status st = smile_validate_desc(desc);
+    if (st != SMILE_OK) return st;
+    *bytes = workspace_layout(*desc).total;
+    return SMILE_OK;
+}
+
+static smile_status make_ctx(const smile_layer_desc *desc, void *workspace, size_t bytes, bool owns, smile_ctx **out)
+{
+    smile_ctx *c = new (std::nothrow) smile_ctx;
+    if (!c) return SMILE_HIP_ERROR;
+    const Layout L = workspace_layout(*desc);
+    char *b = static_cast<char *>(workspace);
+    c->desc = *desc;
+    c->base = workspace;
+    c->bytes = bytes;
+    c->owns = owns;
+    c->ws.block_expert_hist = reinterpret_cast<int32_t *>(b + L.off_block_expert_hist);
+    c->ws.block_group_hist = reinterpret_cast<int32_t *>(b + L.off_block_group_hist);
+    c->ws.block_p_sum = reinterpret_cast<float *>(b + L.off_block_p_sum);
+    c->ws.block_q_sum = reinterpret_cast<float *>(b + L.off_block_q_sum);
+    c->ws.hidden = b + L.off_hidden;
+    *out = c;
+    return SMILE_OK;
+}
+
+smile_status smile_create(const smile_layer_desc *desc, smile_ctx **ctx)
+{
+    if (!ctx) return SMILE_INVALID_ARG;
+    *ctx = nullptr;
+    smile_status st = smile_validate_desc(desc);
+    if (st != SMILE_OK) return st;
+    const Layout L = workspace_layout(*desc);
+    void *p = nullptr;
+    if (hipMalloc(&p, L.total) != hipSuccess) { (void)hipGetLastError(); return SMILE_HIP_ERROR; }
+    st = make_ctx(desc, p, L.total, true, ctx);
+    if (st != SMILE_OK) (void)hipFree(p);
+    return st;
+}
+
+smile_status smile_create_with_workspace(const smile_layer_desc *desc, void *workspace, size_t bytes, smile_ctx **ctx)
+{
+    if (!ctx) return SMILE_INVALID_ARG;
+    *ctx = nullptr;
+    smile_status st = smile_validate_desc(desc);
+    if (st != SMILE_OK) return st;
+    if (!workspace) return SMILE_INVALID_ARG;
+    const Layout L = workspace_layout(*desc);
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || bytes < L.total) return SMILE_WORKSPACE;
+    return make_ctx(desc, workspace, bytes, false, ctx);
+}
+
+smile_status smile_destroy(smile_ctx *ctx)
+{
+    if (!ctx) return SMILE_OK;
+    smile_status st = SMILE_OK;
+    if (ctx->owns && ctx->base && hipFree(ctx->base) != hipSuccess) { (void)hipGetLastError(); st = SMILE_HIP_ERROR; }
+    delete ctx;
+    return st;
+}
+
+smile_status smile_gate_logits(smile_ctx *ctx, const void *x, const void *w_inter, const void *w_intra,
+                               float *logits_inter, float *logits_intra, void *stream)
+{
+    if (!ctx || bad(x) || bad(w_inter) || bad(w_intra) || bad(logits_inter) || bad(logits_intra))
+        return SMILE_INVALID_ARG;
+    if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
+    return from_hip(launch_gate_logits(ctx->desc, x, w_inter, w_intra, logits_inter, logits_intra,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, const float *logits_intra,
+                                 const float *bias_inter, const float *bias_intra,
+                                 int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot,
+                                 float *gate, float *p_top, float *q_top,
+                                 int32_t *group_count, int32_t *local_count, int32_t *expert_count,
+                                 int32_t *kept_count, float *p_sum, float *q_sum, void *stream)
+{
+    if (!ctx || bad(logits_inter) || bad(logits_intra) || bad_opt(bias_inter) || bad_opt(bias_intra) ||
+        bad(group_idx) || bad(local_idx) || bad(pos_in_group) || bad(slot) || bad(gate) || bad(p_top) ||
+        bad(q_top) || bad(group_count) || bad(local_count) || bad(expert_count) || bad(kept_count) ||
+        bad(p_sum) || bad(q_sum))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_route(ctx->desc, ctx->ws, logits_inter, logits_intra, bias_inter, bias_intra,
+                                 group_idx, local_idx, pos_in_group, slot, gate, p_top, q_top, group_count,
+                                 local_count, expert_count, kept_count, p_sum, q_sum,
+                                 static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_idx, const int32_t *local_idx,
+                            const int32_t *slot, void *xe, void *stream)
+{
+    if (!ctx || bad(x) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(xe)) return SMILE_INVALID_ARG;
+    return from_hip(launch_dispatch(ctx->desc, x, group_idx, local_idx, slot, xe, static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                              const void *w1, const void *b1, const void *w2, const void *b2,
+                              void *ye, void *stream)
+{
+    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1) || bad(w2) || bad_opt(b2) || bad(ye))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_expert_ffn(ctx->desc, ctx->ws, xe, kept_count, w1, b1, w2, b2, ye,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,
+                           const int32_t *slot, const float *gate, void *y, void *stream)
+{
+    if (!ctx || bad(ye) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(gate) || bad(y))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_combine(ctx->desc, ye, group_idx, local_idx, slot, gate, y,
+                                   static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_aux_loss(smile_ctx *ctx, const int32_t *group_count, const int32_t *local_count,
+                            const float *p_sum, const float *q_sum, float *out3, void *stream)
+{
+    if (!ctx || bad(group_count) || bad(local_count) || bad(p_sum) || bad(q_sum) || bad(out3))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_aux_loss(ctx->desc, group_count, local_count, p_sum, q_sum, out3,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream)
+{
+    if (!ctx || !io) return SMILE_INVALID_ARG;
+    // check every pointer first so that a bad argument of a late step leaves nothing enqueued
+    if (bad(io->x) || bad(io->w_inter) || bad(io->w_intra) || bad(io->w1) || bad_opt(io->b1) || bad(io->w2) ||
+        bad_opt(io->b2) || bad_opt(io->bias_inter) || bad_opt(io->bias_intra) || bad(io->logits_inter) ||
+        bad(io->logits_intra) || bad(io->group_idx) || bad(io->local_idx) || bad(io->pos_in_group) ||
+        bad(io->slot) || bad(io->gate) || bad(io->p_top) || bad(io->q_top) || bad(io->group_count) ||
+        bad(io->local_count) || bad(io->expert_count) || bad(io->kept_count) || bad(io->p_sum) ||
+        bad(io->q_sum) || bad(io->xe) || bad(io->ye) || bad(io->y) || bad(io->loss3))
+        return SMILE_INVALID_ARG;
+    if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
+    smile_status st;
+    st = smile_gate_logits(ctx, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, stream);
+    if (st != SMILE_OK) return st;
+    st = smile_route_bilevel(ctx, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
+                             io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top,
+                             io->q_top, io->group_count, io->local_count, io->expert_count, io->kept_count,
+                             io->p_sum, io->q_sum, stream);
+    if (st != SMILE_OK) return st;
+    st = smile_dispatch(ctx, io->x, io->group_idx, io->local_idx, io->slot, io->xe, stream);
+    if (st != SMILE_OK) return st;
+    st = smile_expert_ffn(ctx, io->xe, io->kept_count, io->w1, io->b1, io->w2, io->b2, io->ye, stream);
+    if (st != SMILE_OK) return st;
+    st = smile_combine(ctx, io->ye, io->group_idx, io->local_idx, io->slot, io->gate, io->y, stream);
+    if (st != SMILE_OK) return st;
+    return smile_aux_loss(ctx, io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Internal declarations shared by the translation units of libsmile (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "smile.h"
+
+namespace smile {
+
+// tokens handled by one workgroup of the routing kernels
+constexpr int kRouteBlock = 256;
+
+struct Workspace {
+    // routing: per-block histograms turned into exclusive block offsets by the scan kernel
+    int32_t *block_expert_hist;   // [B][N]
+    int32_t *block_group_hist;    // [B][n]
+    float *block_p_sum;           // [B][n]
+    float *block_q_sum;           // [B][m]
+    // expert FFN: hidden activation between the two grouped GEMMs, ctx dtype
+    void *hidden;                 // [N][C][F]
+};
+
+struct Layout {
+    size_t off_block_expert_hist, off_block_group_hist, off_block_p_sum, off_block_q_sum, off_hidden, total;
+    int32_t route_blocks;
+};
+
+Layout workspace_layout(const smile_layer_desc &d);
+
+}  // namespace smile
+
+struct smile_ctx {
+    smile_layer_desc desc;
+    smile::Workspace ws;
+    void *base;
+    size_t bytes;
+    bool owns;
+};
+
+namespace smile {
+
+// Launchers: enqueue on `s`, return the launch status.  Shapes were validated by the caller.
+hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+                              float *logits_inter, float *logits_intra, hipStream_t s);
+
+hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const float *logits_inter,
+                        const float *logits_intra, const float *bias_inter, const float *bias_intra,
+                        int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
+                        float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
+                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s);
+
+hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
+                           const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s);
+
+hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
+                          const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s);
+
+hipError_t launch_expert_ffn(const smile_layer_desc &d, const Workspace &ws, const void *xe,
+                             const int32_t *kept_count, const void *w1, const void *b1, const void *w2,
+                             const void *b2, void *ye, hipStream_t s);
+
+hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
+                           const float *p_sum, const float *q_sum, float *out3, hipStream_t s);
+
+}  // namespace smile

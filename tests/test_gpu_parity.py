@@ -1,0 +1,163 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the same seeded
+inputs.  Small / medium shapes are compared element by element; the full benchmark configurations
+are compared completely for routing and dispatch and on sampled rows for the expert FFN / combine.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2212_05191_amd import binding as B
+from paper_2212_05191_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity  # noqa: E402
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.load()
+    return torch
+
+
+def _run(cfg, forward="steps", **kw):
+    from paper_2212_05191_amd.runner import GpuLayer
+    _say(f"[case] {cfg.name}: T={cfg.T} d={cfg.d_model} F={cfg.d_ff} n={cfg.n_groups} m={cfg.m_local} "
+         f"C={cfg.capacity} {cfg.dtype}/{cfg.act} skew={cfg.skew} forward={forward}")
+    layer = GpuLayer(cfg, **kw)
+    # poison the outputs so that an unwritten element cannot pass by luck
+    for k, v in layer.buf.__dict__.items():
+        if k not in ("xe", "ye"):
+            v.fill_(-77)
+    layer.buf.xe.zero_()
+    layer.buf.ye.zero_()
+    if forward == "steps":
+        layer.forward_steps()
+    else:
+        layer.forward()
+    return layer
+
+
+SMALL = [
+    wl.CONFIGS["cfg1"],
+    wl.small_config("ragged_f32_relu", 777, 72, 136, 3, 5, 37, "f32", "relu", seed=11),
+    wl.small_config("ragged_f32_gelu", 1301, 64, 200, 5, 3, 100, "f32", "gelu", seed=12),
+    wl.small_config("mid_bf16_gelu", 3000, 192, 320, 3, 4, 200, "bf16", "gelu", seed=13),
+    wl.small_config("mid_bf16_relu_skew", 2500, 128, 448, 4, 8, 90, "bf16", "relu", skew=True, seed=14),
+    wl.small_config("one_token", 1, 64, 64, 2, 2, 1, "bf16", "gelu", seed=15),
+    wl.small_config("capacity_one", 300, 64, 128, 2, 3, 1, "bf16", "gelu", seed=16),
+    wl.small_config("single_group", 600, 64, 128, 1, 6, 80, "bf16", "gelu", seed=17),
+    wl.small_config("single_local", 600, 64, 128, 6, 1, 80, "f32", "gelu", seed=18),
+    wl.small_config("one_expert_dense", 200, 128, 256, 1, 1, 200, "bf16", "gelu", seed=19),
+    wl.small_config("many_groups", 5000, 64, 64, 40, 24, 9, "bf16", "relu", seed=20),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_small_shapes_full_parity(torch_cuda, cfg):
+    layer = _run(cfg)
+    try:
+        info = parity.check_full(cfg, layer)
+        _say(f"   {info}")
+    finally:
+        layer.close()
+
+
+def test_chained_entry_point_equals_step_by_step(torch_cuda):
+    cfg = SMALL[3]
+    a = _run(cfg, "steps")
+    b = _run(cfg, "chained", own_workspace=True)
+    try:
+        oa, ob = parity.fetch(a), parity.fetch(b)
+        for k in oa:
+            if k in ("xe", "ye"):
+                continue        # rows beyond kept_count are unspecified
+            np.testing.assert_array_equal(oa[k], ob[k], err_msg=k)
+        parity.check_full(cfg, b)
+    finally:
+        a.close()
+        b.close()
+
+
+def test_repeated_calls_are_bit_identical(torch_cuda):
+    cfg = wl.small_config("determinism", 4099, 128, 256, 4, 8, 100, "bf16", "gelu", skew=True, seed=21)
+    layer = _run(cfg)
+    try:
+        first = parity.fetch(layer)
+        for _ in range(3):
+            layer.forward()
+            again = parity.fetch(layer)
+            for k in first:
+                np.testing.assert_array_equal(first[k], again[k], err_msg=k)
+    finally:
+        layer.close()
+
+
+def test_expert_biases(torch_cuda):
+    """Optional b1 / b2 of the expert FFN (NULL in the benchmark configurations)."""
+    torch = torch_cuda
+    from paper_2212_05191_amd.runner import GpuLayer, to_device, to_host
+    for dtype in ("f32", "bf16"):
+        cfg = wl.small_config(f"biases_{dtype}", 500, 64, 192, 2, 2, 150, dtype, "gelu", seed=22)
+        _say(f"[case] {cfg.name}")
+        layer = GpuLayer(cfg)
+        rng = np.random.default_rng(5)
+        b1 = wl.quantize(rng.standard_normal((cfg.N, cfg.d_ff)).astype(np.float32), dtype)
+        b2 = wl.quantize(rng.standard_normal((cfg.N, cfg.d_model)).astype(np.float32), dtype)
+        layer.b1, layer.b2 = to_device(b1, dtype), to_device(b2, dtype)
+        layer.buf.ye.zero_()
+        layer.forward_steps()
+        out = parity.fetch(layer)
+        x, wi, wq, bi, bq = parity.host_inputs(cfg)
+        r, _ = parity.check_logits_and_routing(cfg, out, x, wi, wq, bi, bq)
+        xe = parity.check_dispatch_exact(cfg, out, x, r)
+        w1 = np.stack([wl.gen_expert_weights(cfg, e)[0] for e in range(cfg.N)])
+        w2 = np.stack([wl.gen_expert_weights(cfg, e)[1] for e in range(cfg.N)])
+        ye = oracle.expert_ffn(xe, r.kept_count, w1, w2, cfg.act, dtype, b1, b2)
+        mask = np.arange(cfg.capacity)[None, :] < r.kept_count[:, None]
+        assert parity.normwise(out["ye"][mask], ye[mask]) <= parity.TOL[dtype]
+        layer.close()
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
+def test_every_ffn_tile_shape(torch_cuda, tile, monkeypatch):
+    """Each MFMA tile shape of the grouped GEMM, on a shape with ragged row and column tiles."""
+    monkeypatch.setenv("SMILE_FFN_TILE", str(tile))
+    cfg = wl.small_config(f"tile{tile}", 4000, 320, 448, 2, 3, 600, "bf16", "gelu", seed=23)
+    layer = _run(cfg)
+    try:
+        _say(f"   {parity.check_full(cfg, layer)}")
+    finally:
+        layer.close()
+
+
+def test_cfg2_full_parity(torch_cuda):
+    cfg = wl.CONFIGS["cfg2"]
+    layer = _run(cfg, "chained")
+    try:
+        _say(f"   {parity.check_full(cfg, layer)}")
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_full_size_configs_sampled_parity(torch_cuda, name):
+    cfg = wl.CONFIGS[name]
+    layer = _run(cfg, "chained", workers=16)
+    try:
+        info = parity.check_sampled(cfg, layer)
+        _say(f"   {info}")
+        if name == "cfg5":
+            assert info["dropped"] > cfg.T // 10, "the skewed configuration must drop many tokens"
+    finally:
+        layer.close()
