@@ -150,6 +150,15 @@ smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kep
                               const void *w1, const void *b1, const void *w2, const void *b2,
                               void *ye, void *stream);
 
+/* The two halves of smile_expert_ffn as separate calls (same kernels, same results), for callers
+ * that want to time or interleave them: _up computes h = act(xe . w1^T + b1) into the ctx
+ * workspace, _down computes ye = h . w2^T + b2 from it.  _down must follow an _up on the same ctx
+ * and stream with the same kept_count. */
+smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                 const void *w1, const void *b1, void *stream);
+smile_status smile_expert_ffn_down(smile_ctx *ctx, const int32_t *kept_count, const void *w2, const void *b2,
+                                   void *ye, void *stream);
+
 /* Step 4 -- combine (Eq. 3): y[t,:] = gate[t] * ye[e, slot[t], :] for kept
  * tokens, 0 for dropped ones; product in fp32, rounded once to the ctx dtype. */
 smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,

@@ -43,7 +43,7 @@ class LayerIO(C.Structure):
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
-    "smile_dispatch", "smile_expert_ffn", "smile_combine", "smile_aux_loss", "smile_layer_forward",
+    "smile_dispatch", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_combine", "smile_aux_loss", "smile_layer_forward",
 )
 
 
@@ -71,6 +71,8 @@ def load() -> C.CDLL:
     lib.smile_route_bilevel.argtypes = [vp] * 19
     lib.smile_dispatch.argtypes = [vp] * 7
     lib.smile_expert_ffn.argtypes = [vp] * 9
+    lib.smile_expert_ffn_up.argtypes = [vp] * 6
+    lib.smile_expert_ffn_down.argtypes = [vp] * 6
     lib.smile_combine.argtypes = [vp] * 8
     lib.smile_aux_loss.argtypes = [vp] * 7
     lib.smile_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]
@@ -187,6 +189,16 @@ def smile_dispatch(ctx: Ctx, x, group_idx, local_idx, slot, xe, stream=None):
 def smile_expert_ffn(ctx: Ctx, xe, kept_count, w1, b1, w2, b2, ye, stream=None):
     _check(load().smile_expert_ffn(ctx.handle, _ptr(xe), _ptr(kept_count), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2),
                                    _ptr(ye), _stream(stream)), "smile_expert_ffn")
+
+
+def smile_expert_ffn_up(ctx: Ctx, xe, kept_count, w1, b1, stream=None):
+    _check(load().smile_expert_ffn_up(ctx.handle, _ptr(xe), _ptr(kept_count), _ptr(w1), _ptr(b1),
+                                      _stream(stream)), "smile_expert_ffn_up")
+
+
+def smile_expert_ffn_down(ctx: Ctx, kept_count, w2, b2, ye, stream=None):
+    _check(load().smile_expert_ffn_down(ctx.handle, _ptr(kept_count), _ptr(w2), _ptr(b2), _ptr(ye),
+                                        _stream(stream)), "smile_expert_ffn_down")
 
 
 def smile_combine(ctx: Ctx, ye, group_idx, local_idx, slot, gate, y, stream=None):

@@ -307,23 +307,28 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 
 }  // namespace
 
-hipError_t launch_expert_ffn(const smile_layer_desc &d, const Workspace &ws, const void *xe,
-                             const int32_t *kept_count, const void *w1, const void *b1, const void *w2,
-                             const void *b2, void *ye, hipStream_t s)
+hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
+                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s)
 {
     const int N = d.n_groups * d.m_local;
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
     if (d.dtype == SMILE_DTYPE_BF16) {
-        GemmArgs g1{xe, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0};
-        hipError_t err = launch_bf16(g1, N, act, pick_tile(N, d.capacity, d.d_ff), s);
-        if (err != hipSuccess) return err;
-        GemmArgs g2{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0};
-        return launch_bf16(g2, N, 0, pick_tile(N, d.capacity, d.d_model), s);
+        GemmArgs g{xe, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0};
+        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff), s);
     }
-    hipError_t err = launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
-                                static_cast<const float *>(b1), static_cast<float *>(ws.hidden), kept_count, N,
-                                d.capacity, d.d_ff, d.d_model, act, s);
-    if (err != hipSuccess) return err;
+    return launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
+                      static_cast<const float *>(b1), static_cast<float *>(ws.hidden), kept_count, N, d.capacity,
+                      d.d_ff, d.d_model, act, s);
+}
+
+hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
+                                  const void *w2, const void *b2, void *ye, hipStream_t s)
+{
+    const int N = d.n_groups * d.m_local;
+    if (d.dtype == SMILE_DTYPE_BF16) {
+        GemmArgs g{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0};
+        return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model), s);
+    }
     return launch_f32(static_cast<const float *>(ws.hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,
                       d.d_model, d.d_ff, 0, s);

@@ -189,14 +189,29 @@ smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_
     return from_hip(launch_dispatch(ctx->desc, x, group_idx, local_idx, slot, xe, static_cast<hipStream_t>(stream)));
 }
 
+smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                 const void *w1, const void *b1, void *stream)
+{
+    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1)) return SMILE_INVALID_ARG;
+    return from_hip(launch_expert_ffn_up(ctx->desc, ctx->ws, xe, kept_count, w1, b1, static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_expert_ffn_down(smile_ctx *ctx, const int32_t *kept_count, const void *w2, const void *b2,
+                                   void *ye, void *stream)
+{
+    if (!ctx || bad(kept_count) || bad(w2) || bad_opt(b2) || bad(ye)) return SMILE_INVALID_ARG;
+    return from_hip(launch_expert_ffn_down(ctx->desc, ctx->ws, kept_count, w2, b2, ye, static_cast<hipStream_t>(stream)));
+}
+
 smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
                               const void *w1, const void *b1, const void *w2, const void *b2,
                               void *ye, void *stream)
 {
     if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1) || bad(w2) || bad_opt(b2) || bad(ye))
         return SMILE_INVALID_ARG;
-    return from_hip(launch_expert_ffn(ctx->desc, ctx->ws, xe, kept_count, w1, b1, w2, b2, ye,
-                                      static_cast<hipStream_t>(stream)));
+    smile_status st = smile_expert_ffn_up(ctx, xe, kept_count, w1, b1, stream);
+    if (st != SMILE_OK) return st;
+    return smile_expert_ffn_down(ctx, kept_count, w2, b2, ye, stream);
 }
 
 smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,

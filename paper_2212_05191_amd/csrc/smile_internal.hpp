@@ -57,9 +57,11 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
 hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
                           const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s);
 
-hipError_t launch_expert_ffn(const smile_layer_desc &d, const Workspace &ws, const void *xe,
-                             const int32_t *kept_count, const void *w1, const void *b1, const void *w2,
-                             const void *b2, void *ye, hipStream_t s);
+// up: hidden = act(xe . w1^T + b1) into ws.hidden;  down: ye = hidden . w2^T + b2
+hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
+                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s);
+hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
+                                  const void *w2, const void *b2, void *ye, hipStream_t s);
 
 hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
                            const float *p_sum, const float *q_sum, float *out3, hipStream_t s);
