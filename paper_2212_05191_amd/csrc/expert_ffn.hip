@@ -8,14 +8,24 @@
 // (8 consecutive k per lane), so tiles go global -> LDS -> registers as 16-byte pieces with no
 // transposition anywhere.
 //
-// bf16 kernel (the hot kernel of the layer): one workgroup computes a BM x BN tile of one expert
-// with v_mfma_f32_32x32x16_bf16, fp32 accumulators, K stepped in 64-element (128-byte) slabs that
-// are double-buffered in LDS: the global loads of slab k+1 are issued before the MFMAs of slab k
-// and written to the other LDS buffer after them, one barrier per slab.  LDS rows are 128 bytes;
-// the 16-byte piece index is XOR-ed with (row & 7) so that the 32 rows a wave reads for one MFMA
-// operand fall on distinct banks.  The weight tile is the MFMA "A" operand and the token tile the
-// "B" operand, so a lane ends up holding 4 consecutive output columns of one token row and the
-// epilogue (bias, activation, round to bf16) stores 8 bytes at a time.
+// bf16 kernel (the hot kernel of the layer).  One workgroup computes a BM x BN tile of one expert
+// with v_mfma_f32_32x32x16_bf16 and fp32 accumulators.
+//   * K is cut into slabs of BK elements.  A slab travels global -> LDS directly
+//     (global_load_lds_dwordx4: no staging registers, no ds_write) into a ring of STAGES buffers
+//     with STAGES-1 slabs in flight.  Per slab: wait until this wave's part has landed (s_waitcnt
+//     vmcnt), one s_barrier (every wave's part landed, and every wave is done reading the buffer
+//     about to be refilled), issue the loads of the slab STAGES-1 ahead, then the MFMAs.
+//   * A direct load writes 64 lanes x 16 bytes to consecutive LDS addresses, i.e. whole rows of a
+//     slab.  The bank swizzle is therefore applied on the global side: the lane that fills position
+//     p of a row fetches piece p ^ f(row), so piece c of a row sits at position c ^ f(row) and the
+//     32 rows a wave reads for one MFMA operand fall on distinct banks.
+//   * The weight tile is the MFMA "A" operand and the token tile the "B" operand, so a lane ends up
+//     with 4 consecutive output columns of one token row.  The epilogue (bias, activation, round
+//     to bf16) writes them to LDS and the workgroup then stores whole rows, 16 bytes per lane, so
+//     every global store instruction covers full cache lines.
+//   * Traffic L2 -> LDS per flop falls as 1/BM + 1/BN; that path (about 64 B/clk per CU at best)
+//     and not HBM is what bounds small tiles, so tiles are as large as the workload can still
+//     spread over 256 CUs.
 //
 // The grid covers every (expert, column tile, row tile); tiles whose first row is >= kept[e] exit
 // at once, so no host synchronisation on the routing result is needed.  Workgroup ids are dealt
@@ -37,15 +47,29 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
 
+// ACT: 0 none, 1 ReLU, 2 GELU (erff; fp32 path), 3 GELU (rational erfc; bf16 path)
 template <int ACT>
 __device__ __forceinline__ float activate(float v)
 {
     if constexpr (ACT == 1) return v > 0.f ? v : 0.f;
     else if constexpr (ACT == 2) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
-    else return v;
+    else if constexpr (ACT == 3) {
+        // GELU(v) = v * Phi(v) = max(v,0) - |v| * erfc(|v|/sqrt2)/2, with erfc from the rational
+        // approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7, far below bf16 resolution):
+        // erfc(z) = (a1 t + ... + a5 t^5) exp(-z^2), t = 1/(1 + p z).  ~14 VALU ops, no branches.
+        const float av = fabsf(v);
+        const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, av, 1.0f));
+        float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+        poly = fmaf(poly, t, 0.5f * 1.421413741f);
+        poly = fmaf(poly, t, 0.5f * -0.284496736f);
+        poly = fmaf(poly, t, 0.5f * 0.254829592f);
+        const float ex = __builtin_amdgcn_exp2f(v * v * (-0.5f * 1.4426950408889634f));
+        return fmaxf(v, 0.f) - av * (poly * t * ex);
+    } else return v;
 }
 
 // ------------------------------------------------------------------------------------ bf16 / MFMA
@@ -60,18 +84,46 @@ struct GemmArgs {
     int row_tiles, col_tiles, tiles;   // tiles = N*row_tiles*col_tiles
 };
 
-template <int BM, int BN, int WGM, int WGN, int ACT>
-__global__ __launch_bounds__(WGM *WGN * 64) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
-{
-    constexpr int NT = WGM * WGN * 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN;        // wave tile
-    constexpr int TM = WM / 32, TN = WN / 32;          // MFMA tiles per wave
-    constexpr int XP = BM * 8 / NT, WP = BN * 8 / NT;  // 16-byte pieces per thread per slab
-    static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32");
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && NT % 8 == 0, "slab must divide over the threads");
+#define SMILE_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define SMILE_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-    __shared__ u32x4 lds_x[2][BM * 8];
-    __shared__ u32x4 lds_w[2][BN * 8];
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);   // expcnt, lgkmcnt: no wait
+}
+
+// Swizzle term of a row: rows are BK*2 bytes; consecutive rows must land on different banks.
+template <int BK, int SWZ>
+__device__ __forceinline__ int swz(int row)
+{
+    if (BK == 64) return SWZ == 0 ? (row & 7) : ((row >> 1) & 7);
+    return SWZ == 0 ? ((row >> 1) & 3) : ((row >> 2) & 3);
+}
+
+// OCC: waves per SIMD the register allocation must leave room for (workgroups per CU when the
+// workgroup has 4 waves).
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT>
+__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
+{
+    constexpr int NW = WGM * WGN, NT = NW * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
+    constexpr int PPR = BK / 8;                   // 16-byte pieces per LDS row
+    constexpr int RPI = 64 / PPR;                 // rows filled by one direct-load instruction
+    constexpr int ROWS = BM + BN;                 // LDS rows per stage: token tile, then weight tile
+    constexpr int GPW = ROWS / RPI / NW;          // load instructions per wave per slab
+    constexpr int STAGE = ROWS * PPR;             // 16-byte units per stage
+    constexpr int OROWS = WGM * 32;               // output rows staged per epilogue pass
+    constexpr int OSTRIDE = BN / 8 + 1;           // staged row length in 16-byte units (+1: bank spread)
+    static_assert(BK == 64 || BK == 32, "slab depth");
+    static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32");
+    static_assert(ROWS % (RPI * NW) == 0 && BM % RPI == 0, "slab must divide into load instructions over the waves");
+    static_assert(STAGES >= 2 && STAGES <= 4 && (STAGES - 2) * GPW < 64, "pipeline depth");
+    static_assert(OROWS * OSTRIDE <= STAGES * STAGE, "epilogue staging must fit in the pipeline buffers");
+
+    __shared__ u32x4 lds[STAGES * STAGE];
 
     // ---- which tile (XCD-aware remap of the hardware's round-robin workgroup placement)
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
@@ -88,30 +140,31 @@ __global__ __launch_bounds__(WGM *WGN * 64) void grouped_gemm_nt_bf16_kernel(Gem
     const __bf16 *X = static_cast<const __bf16 *>(a.x) + (size_t)e * a.C * K;
     const __bf16 *W = static_cast<const __bf16 *>(a.w) + (size_t)e * Nout * K;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
 
-    // ---- global -> LDS: thread moves piece (tid & 7) of rows (tid >> 3) + i * NT/8
-    const int piece = tid & 7, prow = tid >> 3;
-    const __bf16 *xg[XP];
-    const __bf16 *wg[WP];
-    int xl[XP], wl[WP];
+    // ---- this lane's source address in each of the wave's load instructions
+    const int lr = lane / PPR, lp = lane % PPR;
+    const __bf16 *src[GPW];
 #pragma unroll
-    for (int i = 0; i < XP; ++i) {
-        const int r = prow + i * (NT / 8);
-        xg[i] = X + (size_t)min(rt * BM + r, rows - 1) * K + piece * 8;   // rows past the end re-read the last one
-        xl[i] = r * 8 + (piece ^ (r & 7));
+    for (int i = 0; i < GPW; ++i) {
+        const int row = (wave + i * NW) * RPI + lr;            // row of the stage
+        const int piece = lp ^ swz<BK, SWZ>(row);
+        // rows past the end of the expert's tokens / of the weight matrix re-read the last valid one
+        src[i] = row < BM ? X + (size_t)min(rt * BM + row, rows - 1) * K + piece * 8
+                          : W + (size_t)min(ct * BN + row - BM, Nout - 1) * K + piece * 8;
     }
+    auto issue = [&](int slab, int stage) {
 #pragma unroll
-    for (int i = 0; i < WP; ++i) {
-        const int r = prow + i * (NT / 8);
-        wg[i] = W + (size_t)min(ct * BN + r, Nout - 1) * K + piece * 8;
-        wl[i] = r * 8 + (piece ^ (r & 7));
-    }
+        for (int i = 0; i < GPW; ++i)
+            __builtin_amdgcn_global_load_lds(SMILE_GPTR(src[i] + slab * BK),
+                                             SMILE_LPTR(&lds[stage * STAGE + (wave + i * NW) * 64]), 16, 0, 0);
+    };
 
     // ---- LDS -> MFMA operands: lane reads row (lane & 31), pieces 2*kk + (lane >> 5)
-    const int frow = lane & 31, fhi = lane >> 5, fsw = lane & 7;
-    const int xbase = (wm * WM + frow) * 8, wbase = (wn * WN + frow) * 8;
+    const int frow = lane & 31, fhi = lane >> 5, fsw = swz<BK, SWZ>(lane);   // tile bases are multiples of 32
+    const int xbase = (wm * WM + frow) * PPR, wbase = (BM + wn * WN + frow) * PPR;
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -121,78 +174,87 @@ __global__ __launch_bounds__(WGM *WGN * 64) void grouped_gemm_nt_bf16_kernel(Gem
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 xr[XP], wr[WP];
+    const int slabs = K / BK;
 #pragma unroll
-    for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xg[i]);
-#pragma unroll
-    for (int i = 0; i < WP; ++i) wr[i] = *reinterpret_cast<const u32x4 *>(wg[i]);
-#pragma unroll
-    for (int i = 0; i < XP; ++i) lds_x[0][xl[i]] = xr[i];
-#pragma unroll
-    for (int i = 0; i < WP; ++i) lds_w[0][wl[i]] = wr[i];
-    __syncthreads();
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < slabs) issue(s, s);
 
-    const int slabs = K / 64;
+    int stage = 0;
     for (int kt = 0; kt < slabs; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < slabs;
-        if (more) {
-            const int k0 = (kt + 1) * 64;
-#pragma unroll
-            for (int i = 0; i < XP; ++i) xr[i] = *reinterpret_cast<const u32x4 *>(xg[i] + k0);
-#pragma unroll
-            for (int i = 0; i < WP; ++i) wr[i] = *reinterpret_cast<const u32x4 *>(wg[i] + k0);
-        }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 xf[TM], wf[TN];
+        // loads issued after slab kt's: those of the next min(STAGES-2, slabs-1-kt) slabs
+        const int ahead = min(STAGES - 2, slabs - 1 - kt);
+        if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
+        else if (STAGES >= 3 && ahead == 1) wait_vmcnt<GPW>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        const int nxt = kt + STAGES - 1;
+        if (nxt < slabs) issue(nxt, stage == 0 ? STAGES - 1 : stage - 1);
+        const u32x4 *cur = lds + stage * STAGE;
+        // operand fragments are double-buffered in registers: those of k-step kk+1 are requested
+        // before the MFMAs of k-step kk are issued, so LDS latency hides behind matrix work
+        bf16x8 xf[2][TM], wf[2][TN];
+        auto fetch = [&](int buf, int kk) {
             const int p = (2 * kk + fhi) ^ fsw;
 #pragma unroll
-            for (int j = 0; j < TM; ++j) xf[j] = __builtin_bit_cast(bf16x8, lds_x[cur][xbase + j * 256 + p]);
+            for (int j = 0; j < TM; ++j) xf[buf][j] = __builtin_bit_cast(bf16x8, cur[xbase + j * 32 * PPR + p]);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) wf[i] = __builtin_bit_cast(bf16x8, lds_w[cur][wbase + i * 256 + p]);
+            for (int i = 0; i < TN; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, cur[wbase + i * 32 * PPR + p]);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) fetch((kk + 1) & 1, kk + 1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the MFMAs it overlaps with
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < XP; ++i) lds_x[cur ^ 1][xl[i]] = xr[i];
-#pragma unroll
-            for (int i = 0; i < WP; ++i) lds_w[cur ^ 1][wl[i]] = wr[i];
-        }
-        __syncthreads();
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
     }
 
-    // ---- epilogue: accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4, row lane%32)
+    // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4,
+    // row lane%32) of its 32x32 tile.  One pass per 32-row slice of the wave tiles: bias +
+    // activation + rounding, 8-byte writes into a [OROWS][BN] staging tile, then row-contiguous
+    // 16-byte global stores by the whole workgroup.
     __bf16 *Y = static_cast<__bf16 *>(a.y) + (size_t)e * a.C * Nout;
     const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (size_t)e * Nout : nullptr;
+    u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
+    constexpr int OPR = BN / 8;   // 16-byte pieces per output row
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-        const int row = rt * BM + wm * WM + j * 32 + frow;
-        if (row >= rows) continue;
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
+        __builtin_amdgcn_s_barrier();          // main-loop reads / the previous pass's stores are finished
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int col = ct * BN + wn * WN + i * 32 + 8 * q + 4 * fhi;
-                if (col >= Nout) continue;
+                const int lcol = wn * WN + i * 32 + 8 * q + 4 * fhi;      // column inside the tile
                 bf16x4 out;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     float f = acc[i][j][4 * q + v];
-                    if (bias) f += (float)bias[col + v];
+                    if (bias) f += (float)bias[min(ct * BN + lcol + v, Nout - 1)];
                     out[v] = (__bf16)activate<ACT>(f);
                 }
-                *reinterpret_cast<bf16x4 *>(Y + (size_t)row * Nout + col) = out;
+                stg[((wm * 32 + frow) * OSTRIDE) * 2 + (lcol >> 2)] = __builtin_bit_cast(u32x2, out);
             }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        for (int id = tid; id < OROWS * OPR; id += NT) {
+            const int orow = id / OPR, piece = id - orow * OPR;
+            const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
+            const int col = ct * BN + piece * 8;
+            if (row < rows && col < Nout)
+                *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = lds[orow * OSTRIDE + piece];
         }
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
 hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s)
 {
     a.row_tiles = (a.C + BM - 1) / BM;
@@ -200,32 +262,42 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s)
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(WGM * WGN * 64);
-    if (act == 0) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, 0>), grid, block, 0, s, a);
-    else if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, 1>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, 2>), grid, block, 0, s, a);
+    if (act == 0) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>), grid, block, 0, s, a);
+    else if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
-// Tile shapes: id -> (BM, BN, waves along M, waves along N)
+// Tile shapes: id -> (BM, BN, waves along M, waves along N, BK, stages, waves/SIMD budget).
+// Measured on the four bf16 workloads (T=8192..65536, 16..256 experts): 128x192 with two
+// co-resident workgroups per CU is within 5% of the best shape everywhere; when the grid has no
+// more than one such tile per CU the deeper 3-stage variant wins instead.  Larger tiles move fewer
+// bytes L2 -> LDS per flop but leave a single wave per SIMD, which costs more than it saves here.
 hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s)
 {
     switch (tile) {
-    case 0: return launch_bf16_tile<128, 128, 2, 2>(a, N, act, s);
-    case 1: return launch_bf16_tile<256, 128, 2, 2>(a, N, act, s);
-    case 2: return launch_bf16_tile<128, 256, 2, 2>(a, N, act, s);
-    case 3: return launch_bf16_tile<256, 256, 2, 2>(a, N, act, s);
-    case 4: return launch_bf16_tile<256, 256, 2, 4>(a, N, act, s);
-    case 5: return launch_bf16_tile<64, 128, 1, 4>(a, N, act, s);
+    case 0: return launch_bf16_tile<128, 192, 2, 2, 64, 2, 2>(a, N, act, s);
+    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 3, 1>(a, N, act, s);
+    case 2: return launch_bf16_tile<128, 128, 2, 2, 64, 2, 2>(a, N, act, s);
+    case 3: return launch_bf16_tile<128, 256, 2, 2, 32, 3, 2>(a, N, act, s);
+    case 4: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s);
+    case 5: return launch_bf16_tile<256, 192, 4, 2, 64, 2, 2>(a, N, act, s);
+    case 6: return launch_bf16_tile<256, 256, 2, 4, 32, 4, 2>(a, N, act, s);
+    case 7: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s);
     default: return hipErrorInvalidValue;
     }
 }
+constexpr int kNumTiles = 8;
 
-// Heuristic tile choice: the largest tile that still gives every CU at least ~2 tiles of real work.
+// Tile choice; the environment variable SMILE_FFN_TILE (0..7) overrides it for tuning runs.
 int pick_tile(int N, int C, int Nout)
 {
-    if (const char *env = std::getenv("SMILE_FFN_TILE")) return std::atoi(env);
-    (void)N; (void)C; (void)Nout;
-    return 0;
+    if (const char *env = std::getenv("SMILE_FFN_TILE")) {
+        const int t = std::atoi(env);
+        if (t >= 0 && t < kNumTiles) return t;
+    }
+    const long long tiles = (long long)N * ((C + 127) / 128) * ((Nout + 191) / 192);
+    return tiles <= 256 ? 1 : 0;
 }
 
 // ------------------------------------------------------------------------------------ fp32 / FMA
