@@ -6,11 +6,14 @@ logits -> bi-level routing with capacity -> dispatch -> expert FFN (up, down) ->
 all through the C-ABI library, inputs and weights resident in HBM.  The workload is the
 Switch-base-shaped bf16 configuration (T=8192, d=768, F=3072, 2 groups x 8 experts, cf 1.0).
 
-Prints ONE JSON line: tokens/s of the whole layer, the roofline of the dominant kernel (the
-up-projection + GELU grouped GEMM, timed with HIP events on the launch stream inside the timed
-region), per-step times from a second instrumented pass, and the CPU oracle timed on the host cores.
+Prints ONE JSON line: tokens/s of the whole layer (timed region: K calls of smile_layer_forward),
+the roofline of the dominant kernel (the up-projection + GELU grouped GEMM, timed inside the timed
+region with a HIP event pair that the library attaches to that kernel's launch on its stream),
+per-step times from a second, instrumented pass over the six separate entry points, and the CPU
+oracle timed on the host cores.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -22,9 +25,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by a copy kernel of known size; None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel (up-projection GEMM) from the two rocprofv3 --pmc passes
+# summarised in profiles/bench_cfg2_hbm_traffic_pmc.txt: FETCH_SIZE 43047.0 KiB x 1.99981 + WRITE_SIZE
+# 48024.0 KiB x 1.00000 (scale factors = what the same counters read for a plain 256 MiB device copy).
+# Measured for the headline workload only.
+MEASURED_TRAFFIC_BYTES = {"cfg2": 137.33e6}
 
 
 def main():
@@ -34,6 +39,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", help="one of cfg1..cfg5 (cfg2 is the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reads 256 MiB, writes 256 MiB) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE pass of this command has a kernel of known "
+                         "traffic to scale the counters by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (all experts resident on one MI355X); run with --gpus 1",
@@ -54,7 +63,7 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     p = B._ptr
 
-    # pre-marshalled calls: (name, function, args)
+    # pre-marshalled step-by-step calls for the instrumented pass: (name, function, args)
     calls = [
         ("gate_logits", lib.smile_gate_logits,
          (h, p(layer.x), p(layer.w_inter), p(layer.w_intra), p(b.logits_inter), p(b.logits_intra), stream)),
@@ -75,22 +84,35 @@ def main():
     ]
     dominant = 3   # expert_ffn_up
 
+    # raw HIP events (timing enabled) for the dominant kernel: the library passes them to the
+    # launch itself, so they carry the kernel's own begin / end timestamps on its stream
+    hip = ctypes.CDLL("libamdhip64.so")
+
+    def new_event():
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def elapsed_ms(a, z):
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, z) == 0
+        return float(ms.value)
+
+    io = layer.io
+
     def step(ev=None):
-        for i, (name, fn, a) in enumerate(calls):
-            if ev is not None and i == dominant:
-                ev[0].record()
-            st = fn(*a)
-            if st != 0:
-                raise B.SmileError(st, name)
-            if ev is not None and i == dominant:
-                ev[1].record()
+        """One forward pass through the single chained entry point (all steps, fewest launches)."""
+        io.prof_up_start, io.prof_up_stop = (ev[0], ev[1]) if ev is not None else (None, None)
+        st = lib.smile_layer_forward(h, ctypes.byref(io), stream)
+        if st != 0:
+            raise B.SmileError(st, "smile_layer_forward")
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps, one event pair per step around the dominant kernel
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    evs = [(new_event(), new_event()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -98,7 +120,18 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec_per_step = (t1 - t0) / args.steps
-    dom_ms = float(np.mean([a.elapsed_time(z) for a, z in evs]))
+    dom_ms = float(np.mean([elapsed_ms(a, z) for a, z in evs]))
+    for a, z in evs:
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(z)
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     kept = int(b.kept_count.sum().item())
     dropped = cfg.T - kept
@@ -191,7 +224,7 @@ def main():
         "roofline": {"kernel": "grouped_gemm_nt_bf16_kernel (expert FFN up-projection + GELU)",
                      "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES, "avg_launch_us": round(dom_ms * 1e3, 2),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_us": round(dom_ms * 1e3, 2),
                      "alg_flops_per_launch": up_flops},
         "expert_ffn_down_tflops": round(down_tflops, 2),
         "expert_gemm_mfma_frac": round((2 * up_flops) / ((per_call_us["expert_ffn_up"] + per_call_us["expert_ffn_down"])

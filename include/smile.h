@@ -159,6 +159,15 @@ smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *
 smile_status smile_expert_ffn_down(smile_ctx *ctx, const int32_t *kept_count, const void *w2, const void *b2,
                                    void *ye, void *stream);
 
+/* smile_expert_ffn_up with kernel timing, for benchmarks: `start_event` and `stop_event` are
+ * hipEvent_t handles (passed as void*, created by the caller with timing enabled, both non-NULL).
+ * They receive the begin and end timestamps of the up-projection kernel itself, so that
+ * hipEventElapsedTime(start, stop) after synchronisation is the kernel's own duration without
+ * launch gaps.  Same work and results as smile_expert_ffn_up. */
+smile_status smile_expert_ffn_up_timed(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                       const void *w1, const void *b1, void *start_event, void *stop_event,
+                                       void *stream);
+
 /* Step 4 -- combine (Eq. 3): y[t,:] = gate[t] * ye[e, slot[t], :] for kept
  * tokens, 0 for dropped ones; product in fp32, rounded once to the ctx dtype. */
 smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,
@@ -186,11 +195,16 @@ typedef struct smile_layer_io {
     float *p_sum, *q_sum;
     void *xe, *ye, *y;
     float *loss3;
+    /* optional: hipEvent_t pair (both or neither) receiving the begin / end timestamps of the
+     * up-projection kernel, as in smile_expert_ffn_up_timed; NULL = no timing */
+    void *prof_up_start, *prof_up_stop;
 } smile_layer_io;
 
-/* Convenience: enqueue the six steps above in order on `stream`
- * (gate logits, route, dispatch, expert FFN, combine, loss).  Same checks,
- * same results as calling them one by one. */
+/* The whole forward pass in one call: enqueues the six steps above in order on
+ * `stream` (gate logits, route, dispatch, expert FFN, combine, loss).  Same checks
+ * and bit-identical results as calling them one by one, with two kernel launches
+ * fewer (the loss is produced by the routing scan kernel, and the last routing
+ * step runs inside the dispatch kernel). */
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
 
 #ifdef __cplusplus

@@ -37,13 +37,13 @@ class LayerIO(C.Structure):
         "x", "w_inter", "w_intra", "w1", "b1", "w2", "b2", "bias_inter", "bias_intra",
         "logits_inter", "logits_intra", "group_idx", "local_idx", "pos_in_group", "slot",
         "gate", "p_top", "q_top", "group_count", "local_count", "expert_count", "kept_count",
-        "p_sum", "q_sum", "xe", "ye", "y", "loss3")]
+        "p_sum", "q_sum", "xe", "ye", "y", "loss3", "prof_up_start", "prof_up_stop")]
 
 
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
-    "smile_dispatch", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_combine", "smile_aux_loss", "smile_layer_forward",
+    "smile_dispatch", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
 )
 
 
@@ -73,6 +73,7 @@ def load() -> C.CDLL:
     lib.smile_expert_ffn.argtypes = [vp] * 9
     lib.smile_expert_ffn_up.argtypes = [vp] * 6
     lib.smile_expert_ffn_down.argtypes = [vp] * 6
+    lib.smile_expert_ffn_up_timed.argtypes = [vp] * 8
     lib.smile_combine.argtypes = [vp] * 8
     lib.smile_aux_loss.argtypes = [vp] * 7
     lib.smile_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]

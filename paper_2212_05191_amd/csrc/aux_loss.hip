@@ -7,30 +7,12 @@ namespace smile {
 
 namespace {
 
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
-
 __global__ __launch_bounds__(64) void aux_loss_kernel(
     const int32_t *__restrict__ group_count, const int32_t *__restrict__ local_count,
     const float *__restrict__ p_sum, const float *__restrict__ q_sum, int T, int n, int m,
     float alpha, float beta, float *__restrict__ out3)
 {
-    const int lane = threadIdx.x;
-    const float inv_t = 1.0f / (float)T;
-    float a = 0.f, b = 0.f;
-    for (int i = lane; i < n; i += 64) a += ((float)group_count[i] * inv_t) * (p_sum[i] * inv_t);
-    for (int j = lane; j < m; j += 64) b += ((float)local_count[j] * inv_t) * (q_sum[j] * inv_t);
-    a = wave_sum(a) * (float)n;
-    b = wave_sum(b) * (float)m;
-    if (lane == 0) {
-        out3[0] = a;
-        out3[1] = b;
-        out3[2] = alpha * a + beta * b;
-    }
+    aux_loss_wave(group_count, local_count, p_sum, q_sum, T, n, m, alpha, beta, out3);
 }
 
 }  // namespace

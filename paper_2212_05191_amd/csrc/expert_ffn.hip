@@ -36,6 +36,8 @@
 // fp32 kernel (small / reference-precision configurations): classic LDS-tiled FMA GEMM.
 #include <cstdlib>
 
+#include <hip/hip_ext.h>
+
 #include "smile_internal.hpp"
 
 namespace smile {
@@ -254,17 +256,25 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     }
 }
 
+// t0/t1 (both or neither): events that receive the begin / end timestamps of the kernel itself.
+template <typename Kernel>
+void launch_timed(Kernel k, dim3 grid, dim3 block, hipStream_t s, hipEvent_t t0, hipEvent_t t1, const GemmArgs &a)
+{
+    if (t0 && t1) hipExtLaunchKernelGGL(k, grid, block, 0, s, t0, t1, 0, a);
+    else hipLaunchKernelGGL(k, grid, block, 0, s, a);
+}
+
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
-hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s)
+hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(WGM * WGN * 64);
-    if (act == 0) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>), grid, block, 0, s, a);
-    else if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>), grid, block, 0, s, a);
+    if (act == 0) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
+    else if (act == 1) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
+    else launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
     return hipGetLastError();
 }
 
@@ -273,17 +283,18 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s)
 // co-resident workgroups per CU is within 5% of the best shape everywhere; when the grid has no
 // more than one such tile per CU the deeper 3-stage variant wins instead.  Larger tiles move fewer
 // bytes L2 -> LDS per flop but leave a single wave per SIMD, which costs more than it saves here.
-hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s)
+hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
+                       hipEvent_t t1 = nullptr)
 {
     switch (tile) {
-    case 0: return launch_bf16_tile<128, 192, 2, 2, 64, 2, 2>(a, N, act, s);
-    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 3, 1>(a, N, act, s);
-    case 2: return launch_bf16_tile<128, 128, 2, 2, 64, 2, 2>(a, N, act, s);
-    case 3: return launch_bf16_tile<128, 256, 2, 2, 32, 3, 2>(a, N, act, s);
-    case 4: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s);
-    case 5: return launch_bf16_tile<256, 192, 4, 2, 64, 2, 2>(a, N, act, s);
-    case 6: return launch_bf16_tile<256, 256, 2, 4, 32, 4, 2>(a, N, act, s);
-    case 7: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s);
+    case 0: return launch_bf16_tile<128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
+    case 2: return launch_bf16_tile<128, 128, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 3: return launch_bf16_tile<128, 256, 2, 2, 32, 3, 2>(a, N, act, s, t0, t1);
+    case 4: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
+    case 5: return launch_bf16_tile<256, 192, 4, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 6: return launch_bf16_tile<256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 7: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
     default: return hipErrorInvalidValue;
     }
 }
@@ -380,17 +391,21 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 }  // namespace
 
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
-                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s)
+                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
+                                hipEvent_t t0, hipEvent_t t1)
 {
     const int N = d.n_groups * d.m_local;
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
     if (d.dtype == SMILE_DTYPE_BF16) {
         GemmArgs g{xe, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0};
-        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff), s);
+        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff), s, t0, t1);
     }
-    return launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
-                      static_cast<const float *>(b1), static_cast<float *>(ws.hidden), kept_count, N, d.capacity,
-                      d.d_ff, d.d_model, act, s);
+    if (t0 && t1) (void)hipEventRecord(t0, s);
+    const hipError_t err = launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
+                                      static_cast<const float *>(b1), static_cast<float *>(ws.hidden), kept_count, N,
+                                      d.capacity, d.d_ff, d.d_model, act, s);
+    if (t0 && t1) (void)hipEventRecord(t1, s);
+    return err;
 }
 
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,

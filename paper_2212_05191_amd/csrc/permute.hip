@@ -45,6 +45,47 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
         if (dst[i] >= 0) xe[dst[i]] = v[i];
 }
 
+// Dispatch fused with the last routing step (the chained forward pass): every thread derives the
+// token's final slot from the workspace (block offset of its expert + rank inside the block,
+// dropped at or beyond C); the thread moving piece 0 of a token also writes slot / pos_in_group.
+__global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
+    const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
+    const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
+    int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, u32x4 *__restrict__ xe,
+    long long total, int ppr, int n, int m, int C)
+{
+    const long long stride = (long long)gridDim.x * kThreads;
+    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const int N = n * m;
+    u32x4 v[kPieces];
+    long long dst[kPieces];
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+        const long long p = id + i * stride;
+        dst[i] = -1;
+        if (p < total) {
+            const int t = (int)(p / ppr);
+            const int c = (int)(p - (long long)t * ppr);
+            const int b = t / kRouteBlock;
+            const int g = group_idx[t], e = g * m + local_idx[t];
+            const int rank = block_expert_off[(size_t)b * N + e] + rank_in_block[t];
+            const int sl = rank < C ? rank : -1;
+            if (c == 0) {
+                slot[t] = sl;
+                pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
+            }
+            if (sl >= 0) {
+                dst[i] = ((long long)e * C + sl) * ppr + c;
+                v[i] = x[p];
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i)
+        if (dst[i] >= 0) xe[dst[i]] = v[i];
+}
+
 template <bool kBf16>
 __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 {
@@ -120,6 +161,20 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
     hipLaunchKernelGGL(dispatch_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
                        static_cast<const u32x4 *>(x), group_idx, local_idx, slot, static_cast<u32x4 *>(xe), total,
                        ppr, d.m_local, d.capacity);
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
+                                    const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
+                                    int32_t *slot, void *xe, hipStream_t s)
+{
+    const int esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
+    const int ppr = d.d_model * esz / 16;
+    const long long total = (long long)d.T * ppr;
+    hipLaunchKernelGGL(dispatch_finalize_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
+                       static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist, ws.block_group_hist,
+                       ws.rank_in_block, ws.pos_in_block, pos_in_group, slot, static_cast<u32x4 *>(xe), total, ppr,
+                       d.n_groups, d.m_local, d.capacity);
     return hipGetLastError();
 }
 

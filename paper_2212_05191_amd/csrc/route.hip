@@ -7,8 +7,10 @@
 //                  with the same group / the same expert (wave64 ballots + LDS counters); per-block
 //                  histograms.
 //   route_scan     one workgroup: exclusive scan of the block histograms along the block axis (turning
-//                  them into block offsets), totals, kept counts, and the fixed-order sums of p and q.
+//                  them into block offsets; one wave per column, 64 blocks per shuffle scan), totals,
+//                  kept counts, and the fixed-order sums of p and q.
 //   route_finalize one thread per token: global rank = block offset + in-block rank; capacity cut.
+//                  (The chained forward pass skips this kernel and does the same inside dispatch.)
 //
 // Everything that decides an integer is integer arithmetic or an fp32 compare of the caller's logits,
 // so the result depends only on the logits and the token order, never on the launch geometry.  No
@@ -159,51 +161,84 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     block_column_sums(rq, bq, m, mx_q, iz_q, valid, tile, part, block_q_sum + (size_t)b * m);
 }
 
+// Exclusive scan along the block axis of one histogram column (64 blocks per step, one per lane,
+// Hillis-Steele over the wave); returns the column total.  hist[b*stride + col] is rewritten in place.
+__device__ __forceinline__ int wave_scan_column(int32_t *__restrict__ hist, int B, int stride, int col)
+{
+    const int lane = __lane_id();
+    int carry = 0;
+    for (int b0 = 0; b0 < B; b0 += 64) {
+        const int b = b0 + lane;
+        const int v = b < B ? hist[(size_t)b * stride + col] : 0;
+        int incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        if (b < B) hist[(size_t)b * stride + col] = carry + incl - v;
+        carry += __shfl(incl, 63, 64);
+    }
+    return carry;
+}
+
+// Sum over blocks of one column of per-block partial sums, in a fixed order: lane l adds blocks
+// l, l+64, ... serially, then a fixed butterfly over the wave.
+__device__ __forceinline__ float wave_sum_column(const float *__restrict__ part, int B, int stride, int col)
+{
+    float s = 0.f;
+    for (int b = __lane_id(); b < B; b += 64) s += part[(size_t)b * stride + col];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+}
+
+// One workgroup of 16 waves; each wave takes columns wave, wave+16, ... of the work list
+// [N expert columns | n group columns | n p-sum columns | m q-sum columns].
 __global__ __launch_bounds__(1024) void route_scan_kernel(
     int B, int n, int m, int C,
     int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ block_group_hist,
     const float *__restrict__ block_p_sum, const float *__restrict__ block_q_sum,
     int32_t *__restrict__ group_count, int32_t *__restrict__ local_count,
     int32_t *__restrict__ expert_count, int32_t *__restrict__ kept_count,
-    float *__restrict__ p_sum, float *__restrict__ q_sum)
+    float *__restrict__ p_sum, float *__restrict__ q_sum,
+    int T, float alpha, float beta, float *__restrict__ loss3)
 {
-    extern __shared__ int32_t ecnt[];   // [N]
+    extern __shared__ int32_t ecnt[];   // [N] expert totals, [n] group totals, [m] local totals, then float [n], [m]
     const int N = n * m;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    for (int e = tid; e < N; e += nt) {
-        int run = 0;
-        for (int b = 0; b < B; ++b) {
-            const int v = block_expert_hist[(size_t)b * N + e];
-            block_expert_hist[(size_t)b * N + e] = run;
-            run += v;
+    int32_t *gcnt = ecnt + N, *lcnt = gcnt + n;
+    float *psum = reinterpret_cast<float *>(lcnt + m), *qsum = psum + n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
+    const int work = N + 2 * n + m;
+    for (int w = wave; w < work; w += waves) {
+        if (w < N) {
+            const int total = wave_scan_column(block_expert_hist, B, N, w);
+            if (lane == 0) {
+                ecnt[w] = total;
+                expert_count[w] = total;
+                kept_count[w] = min(total, C);
+            }
+        } else if (w < N + n) {
+            const int total = wave_scan_column(block_group_hist, B, n, w - N);
+            if (lane == 0) { gcnt[w - N] = total; group_count[w - N] = total; }
+        } else if (w < N + 2 * n) {
+            const float s = wave_sum_column(block_p_sum, B, n, w - N - n);
+            if (lane == 0) { psum[w - N - n] = s; p_sum[w - N - n] = s; }
+        } else {
+            const float s = wave_sum_column(block_q_sum, B, m, w - N - 2 * n);
+            if (lane == 0) { qsum[w - N - 2 * n] = s; q_sum[w - N - 2 * n] = s; }
         }
-        ecnt[e] = run;
-        expert_count[e] = run;
-        kept_count[e] = min(run, C);
-    }
-    // groups, and the probability sums, go to the threads from the top so they overlap the experts
-    for (int i = nt - 1 - tid; i < n; i += nt) {
-        int run = 0;
-        for (int b = 0; b < B; ++b) {
-            const int v = block_group_hist[(size_t)b * n + i];
-            block_group_hist[(size_t)b * n + i] = run;
-            run += v;
-        }
-        group_count[i] = run;
-        float s = 0.f;
-        for (int b = 0; b < B; ++b) s += block_p_sum[(size_t)b * n + i];
-        p_sum[i] = s;
-    }
-    for (int j = nt - 1 - tid; j < m; j += nt) {
-        float s = 0.f;
-        for (int b = 0; b < B; ++b) s += block_q_sum[(size_t)b * m + j];
-        q_sum[j] = s;
     }
     __syncthreads();
-    for (int j = tid; j < m; j += nt) {
+    for (int j = tid; j < m; j += blockDim.x) {
         int s = 0;
         for (int i = 0; i < n; ++i) s += ecnt[i * m + j];
+        lcnt[j] = s;
         local_count[j] = s;
+    }
+    if (loss3) {   // Eq. 4 right here saves the separate loss launch of the chained forward pass
+        __syncthreads();
+        if (wave == 0) aux_loss_wave(gcnt, lcnt, psum, qsum, T, n, m, alpha, beta, loss3);
     }
 }
 
@@ -211,6 +246,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_finalize_kernel(
     int T, int n, int m, int C,
     const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
+    const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
     int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot)
 {
     const int b = blockIdx.x;
@@ -218,9 +254,9 @@ __global__ __launch_bounds__(kRouteBlock) void route_finalize_kernel(
     if (t >= T) return;
     const int g = group_idx[t], l = local_idx[t];
     const int N = n * m;
-    const int rank = block_expert_off[(size_t)b * N + g * m + l] + slot[t];
+    const int rank = block_expert_off[(size_t)b * N + g * m + l] + rank_in_block[t];
     slot[t] = rank < C ? rank : -1;
-    pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_group[t];
+    pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
 }
 
 int ceil_log2(int v)
@@ -236,24 +272,27 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                         const float *logits_intra, const float *bias_inter, const float *bias_intra,
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
-                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s)
+                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
+                        bool finalize, float *loss3)
 {
     const int n = d.n_groups, m = d.m_local, N = n * m;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
     const size_t lds1 = sizeof(int32_t) * (size_t)(N + n);
     hipLaunchKernelGGL(route_decide_kernel, dim3(B), dim3(kRouteBlock), lds1, s, logits_inter, logits_intra,
                        bias_inter, bias_intra, d.T, n, m, ceil_log2(n), ceil_log2(N), group_idx, local_idx,
-                       pos_in_group, slot, gate, p_top, q_top, ws.block_expert_hist, ws.block_group_hist,
-                       ws.block_p_sum, ws.block_q_sum);
+                       ws.pos_in_block, ws.rank_in_block, gate, p_top, q_top, ws.block_expert_hist,
+                       ws.block_group_hist, ws.block_p_sum, ws.block_q_sum);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), sizeof(int32_t) * (size_t)N, s, B, n, m,
-                       d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
-                       group_count, local_count, expert_count, kept_count, p_sum, q_sum);
+    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), sizeof(int32_t) * (size_t)(N + 2 * n + 2 * m), s, B,
+                       n, m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
+                       group_count, local_count, expert_count, kept_count, p_sum, q_sum, d.T, d.alpha, d.beta,
+                       loss3);
     err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess || !finalize) return err;
     hipLaunchKernelGGL(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,
-                       local_idx, ws.block_expert_hist, ws.block_group_hist, pos_in_group, slot);
+                       local_idx, ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block,
+                       pos_in_group, slot);
     return hipGetLastError();
 }
 

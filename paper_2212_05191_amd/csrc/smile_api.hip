@@ -22,6 +22,8 @@ Layout workspace_layout(const smile_layer_desc &d)
     L.off_block_group_hist = off;  off = align_up(off + B * d.n_groups * sizeof(int32_t), 256);
     L.off_block_p_sum = off;       off = align_up(off + B * d.n_groups * sizeof(float), 256);
     L.off_block_q_sum = off;       off = align_up(off + B * d.m_local * sizeof(float), 256);
+    L.off_rank_in_block = off;     off = align_up(off + (size_t)d.T * sizeof(int32_t), 256);
+    L.off_pos_in_block = off;      off = align_up(off + (size_t)d.T * sizeof(int32_t), 256);
     L.off_hidden = off;            off = align_up(off + N * (size_t)d.capacity * d.d_ff * esz, 256);
     L.total = off;
     return L;
@@ -114,6 +116,8 @@ static smile_status make_ctx(const smile_layer_desc *desc, void *workspace, size
     c->ws.block_group_hist = reinterpret_cast<int32_t *>(b + L.off_block_group_hist);
     c->ws.block_p_sum = reinterpret_cast<float *>(b + L.off_block_p_sum);
     c->ws.block_q_sum = reinterpret_cast<float *>(b + L.off_block_q_sum);
+    c->ws.rank_in_block = reinterpret_cast<int32_t *>(b + L.off_rank_in_block);
+    c->ws.pos_in_block = reinterpret_cast<int32_t *>(b + L.off_pos_in_block);
     c->ws.hidden = b + L.off_hidden;
     *out = c;
     return SMILE_OK;
@@ -196,6 +200,16 @@ smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *
     return from_hip(launch_expert_ffn_up(ctx->desc, ctx->ws, xe, kept_count, w1, b1, static_cast<hipStream_t>(stream)));
 }
 
+smile_status smile_expert_ffn_up_timed(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                       const void *w1, const void *b1, void *start_event, void *stop_event,
+                                       void *stream)
+{
+    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1) || !start_event || !stop_event)
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_expert_ffn_up(ctx->desc, ctx->ws, xe, kept_count, w1, b1, static_cast<hipStream_t>(stream),
+                                         static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)));
+}
+
 smile_status smile_expert_ffn_down(smile_ctx *ctx, const int32_t *kept_count, const void *w2, const void *b2,
                                    void *ye, void *stream)
 {
@@ -244,21 +258,28 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         bad(io->q_sum) || bad(io->xe) || bad(io->ye) || bad(io->y) || bad(io->loss3))
         return SMILE_INVALID_ARG;
     if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
-    smile_status st;
-    st = smile_gate_logits(ctx, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, stream);
-    if (st != SMILE_OK) return st;
-    st = smile_route_bilevel(ctx, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
-                             io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top,
-                             io->q_top, io->group_count, io->local_count, io->expert_count, io->kept_count,
-                             io->p_sum, io->q_sum, stream);
-    if (st != SMILE_OK) return st;
-    st = smile_dispatch(ctx, io->x, io->group_idx, io->local_idx, io->slot, io->xe, stream);
-    if (st != SMILE_OK) return st;
-    st = smile_expert_ffn(ctx, io->xe, io->kept_count, io->w1, io->b1, io->w2, io->b2, io->ye, stream);
-    if (st != SMILE_OK) return st;
-    st = smile_combine(ctx, io->ye, io->group_idx, io->local_idx, io->slot, io->gate, io->y, stream);
-    if (st != SMILE_OK) return st;
-    return smile_aux_loss(ctx, io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3, stream);
+    if ((io->prof_up_start == nullptr) != (io->prof_up_stop == nullptr)) return SMILE_INVALID_ARG;
+    // Same kernels as the step-by-step calls, with two launches saved: the loss comes out of the
+    // routing scan kernel and the last routing step (block offset + rank, capacity cut) runs
+    // inside the dispatch kernel.
+    const smile_layer_desc &d = ctx->desc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err = launch_gate_logits(d, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, s);
+    if (err == hipSuccess)
+        err = launch_route(d, ctx->ws, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
+                           io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top, io->q_top,
+                           io->group_count, io->local_count, io->expert_count, io->kept_count, io->p_sum, io->q_sum,
+                           s, /*finalize=*/false, io->loss3);
+    if (err == hipSuccess)
+        err = launch_dispatch_finalize(d, ctx->ws, io->x, io->group_idx, io->local_idx, io->pos_in_group, io->slot,
+                                       io->xe, s);
+    if (err == hipSuccess)
+        err = launch_expert_ffn_up(d, ctx->ws, io->xe, io->kept_count, io->w1, io->b1, s,
+                                   static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop));
+    if (err == hipSuccess) err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, io->ye, s);
+    if (err == hipSuccess)
+        err = launch_combine(d, io->ye, io->group_idx, io->local_idx, io->slot, io->gate, io->y, s);
+    return from_hip(err);
 }
 
 }  // extern "C"

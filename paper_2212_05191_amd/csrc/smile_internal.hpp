@@ -18,16 +18,44 @@ struct Workspace {
     int32_t *block_group_hist;    // [B][n]
     float *block_p_sum;           // [B][n]
     float *block_q_sum;           // [B][m]
+    int32_t *rank_in_block;       // [T] rank among earlier tokens of the same block with the same expert
+    int32_t *pos_in_block;        // [T] ... with the same group
     // expert FFN: hidden activation between the two grouped GEMMs, ctx dtype
     void *hidden;                 // [N][C][F]
 };
 
 struct Layout {
-    size_t off_block_expert_hist, off_block_group_hist, off_block_p_sum, off_block_q_sum, off_hidden, total;
+    size_t off_block_expert_hist, off_block_group_hist, off_block_p_sum, off_block_q_sum, off_rank_in_block,
+        off_pos_in_block, off_hidden, total;
     int32_t route_blocks;
 };
 
 Layout workspace_layout(const smile_layer_desc &d);
+
+// Eq. 4 on one wave (64 lanes): lane-strided serial sums, fixed butterfly.  Shared by the stand-alone
+// loss kernel and the routing scan kernel so that both give identical bits.
+__device__ __forceinline__ void aux_loss_wave(const int32_t *group_count, const int32_t *local_count,
+                                              const float *p_sum, const float *q_sum, int T, int n, int m,
+                                              float alpha, float beta, float *out3)
+{
+    const int lane = threadIdx.x & 63;
+    const float inv_t = 1.0f / (float)T;
+    float a = 0.f, b = 0.f;
+    for (int i = lane; i < n; i += 64) a += ((float)group_count[i] * inv_t) * (p_sum[i] * inv_t);
+    for (int j = lane; j < m; j += 64) b += ((float)local_count[j] * inv_t) * (q_sum[j] * inv_t);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off, 64);
+        b += __shfl_xor(b, off, 64);
+    }
+    a *= (float)n;
+    b *= (float)m;
+    if (lane == 0) {
+        out3[0] = a;
+        out3[1] = b;
+        out3[2] = alpha * a + beta * b;
+    }
+}
 
 }  // namespace smile
 
@@ -45,21 +73,32 @@ namespace smile {
 hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
                               float *logits_inter, float *logits_intra, hipStream_t s);
 
+// finalize = false leaves pos_in_group / slot unwritten (the block-local ranks stay in the workspace
+// for launch_dispatch_finalize); loss3 != nullptr also writes the Eq. 4 loss from the scan kernel.
 hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const float *logits_inter,
                         const float *logits_intra, const float *bias_inter, const float *bias_intra,
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
-                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s);
+                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
+                        bool finalize = true, float *loss3 = nullptr);
 
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s);
+
+// dispatch fused with the last routing step: computes pos_in_group / slot from the workspace ranks
+// and block offsets, writes them, and moves the rows
+hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
+                                    const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
+                                    int32_t *slot, void *xe, hipStream_t s);
 
 hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
                           const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s);
 
 // up: hidden = act(xe . w1^T + b1) into ws.hidden;  down: ye = hidden . w2^T + b2
+// t0/t1: optional events receiving the begin/end timestamps of the up kernel itself (both or neither)
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
-                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s);
+                                const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
+                                hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
                                   const void *w2, const void *b2, void *ye, hipStream_t s);
 
