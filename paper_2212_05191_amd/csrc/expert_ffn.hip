@@ -35,6 +35,7 @@
 //
 // fp32 kernel (small / reference-precision configurations): classic LDS-tiled FMA GEMM.
 #include <cstdlib>
+#include <type_traits>
 
 #include <hip/hip_ext.h>
 
@@ -182,18 +183,25 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
         if (s < slabs) issue(s, s);
 
     int stage = 0;
-    for (int kt = 0; kt < slabs; ++kt) {
-        // loads issued after slab kt's: those of the next min(STAGES-2, slabs-1-kt) slabs
-        const int ahead = min(STAGES - 2, slabs - 1 - kt);
-        if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
-        else if (STAGES >= 3 && ahead == 1) wait_vmcnt<GPW>();
-        else wait_vmcnt<0>();
+    // One K slab.  ISSUE: this iteration also issues the loads of slab kt+STAGES-1 (always true in
+    // the steady state, false in the last STAGES-1 iterations).  The loads are spread over the
+    // k-steps and the instruction order is pinned (sched_group_barrier: one MFMA, one LDS read, ...,
+    // then the k-step's share of the global loads) so that the three pipes stay busy together
+    // instead of in bursts.
+    auto slab_step = [&](auto issue_tag, int kt) {
+        constexpr bool ISSUE = decltype(issue_tag)::value;
+        if (ISSUE) {
+            wait_vmcnt<(STAGES - 2) * GPW>();
+        } else {
+            const int ahead = slabs - 1 - kt;   // 0 .. STAGES-2 slabs were issued after this one
+            if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
+            else if (STAGES >= 3 && ahead == 1) wait_vmcnt<GPW>();
+            else wait_vmcnt<0>();
+        }
         __builtin_amdgcn_s_barrier();
+        const int nstage = stage == 0 ? STAGES - 1 : stage - 1;
         const int nxt = kt + STAGES - 1;
-        if (nxt < slabs) issue(nxt, stage == 0 ? STAGES - 1 : stage - 1);
         const u32x4 *cur = lds + stage * STAGE;
-        // operand fragments are double-buffered in registers: those of k-step kk+1 are requested
-        // before the MFMAs of k-step kk are issued, so LDS latency hides behind matrix work
         bf16x8 xf[2][TM], wf[2][TN];
         auto fetch = [&](int buf, int kk) {
             const int p = (2 * kk + fhi) ^ fsw;
@@ -202,20 +210,42 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
 #pragma unroll
             for (int i = 0; i < TN; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, cur[wbase + i * 32 * PPR + p]);
         };
+        constexpr int KS = BK / 16;
         fetch(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) fetch((kk + 1) & 1, kk + 1);
-            __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the MFMAs it overlaps with
+        for (int kk = 0; kk < KS; ++kk) {
+            // this k-step's share of the next slab's load instructions
+            constexpr int dummy = 0; (void)dummy;
+            const int l0 = GPW * kk / KS, l1 = GPW * (kk + 1) / KS;
+            if (kk + 1 < KS) fetch((kk + 1) & 1, kk + 1);
+            if (ISSUE) {
+#pragma unroll
+                for (int i = 0; i < GPW; ++i)
+                    if (i >= l0 && i < l1)
+                        __builtin_amdgcn_global_load_lds(SMILE_GPTR(src[i] + nxt * BK),
+                                                         SMILE_LPTR(&lds[nstage * STAGE + (wave + i * NW) * 64]), 16, 0, 0);
+            }
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j], 0, 0, 0);
+            // order inside the k-step: MFMA, LDS read, MFMA, LDS read, ... then MFMA + global loads
+            constexpr int NM = TM * TN, ND = TM + TN;
+#pragma unroll
+            for (int r = 0; r < NM; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
+                if (kk + 1 < KS && r < ND) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+                if (ISSUE && r >= NM - (l1 - l0) ) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global load
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         stage = stage + 1 == STAGES ? 0 : stage + 1;
-    }
+    };
+    int kt = 0;
+    for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
+    for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
 
     // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4,
     // row lane%32) of its 32x32 tile.  One pass per 32-row slice of the wave tiles: bias +
@@ -279,36 +309,40 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
 }
 
 // Tile shapes: id -> (BM, BN, waves along M, waves along N, BK, stages, waves/SIMD budget).
-// Measured on the four bf16 workloads (T=8192..65536, 16..256 experts): 128x192 with two
-// co-resident workgroups per CU is within 5% of the best shape everywhere; when the grid has no
-// more than one such tile per CU the deeper 3-stage variant wins instead.  Larger tiles move fewer
-// bytes L2 -> LDS per flop but leave a single wave per SIMD, which costs more than it saves here.
+// Measured on the four bf16 workloads (T = 8192..65536, 16..256 experts, see the design notes):
+//   * up-projection (short K = d_model, wide output, GELU epilogue): 128x192 with two stages and two
+//     co-resident workgroups per CU wins everywhere -- the second workgroup's MFMAs cover the first
+//     one's prologue latency and activation epilogue;
+//   * down-projection (long K = d_ff, narrow output): a single workgroup per CU with a deeper ring
+//     wins -- four stages of 128x192 when the grid has at most one tile per CU, else three stages
+//     of 128x256 (fewer weight bytes through L2 per flop).
+// Larger tiles (256x128 .. 256x256) move fewer bytes L2 -> LDS per flop but were never faster here.
 hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
                        hipEvent_t t1 = nullptr)
 {
     switch (tile) {
     case 0: return launch_bf16_tile<128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
-    case 2: return launch_bf16_tile<128, 128, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 3: return launch_bf16_tile<128, 256, 2, 2, 32, 3, 2>(a, N, act, s, t0, t1);
-    case 4: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
-    case 5: return launch_bf16_tile<256, 192, 4, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
+    case 2: return launch_bf16_tile<128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
+    case 3: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
+    case 4: return launch_bf16_tile<128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 5: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
     case 6: return launch_bf16_tile<256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
-    case 7: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
     default: return hipErrorInvalidValue;
     }
 }
-constexpr int kNumTiles = 8;
+constexpr int kNumTiles = 7;
 
-// Tile choice; the environment variable SMILE_FFN_TILE (0..7) overrides it for tuning runs.
-int pick_tile(int N, int C, int Nout)
+// Tile choice; the environment variable SMILE_FFN_TILE (0..6) overrides it for tuning runs.
+int pick_tile(int N, int C, int Nout, int K)
 {
     if (const char *env = std::getenv("SMILE_FFN_TILE")) {
         const int t = std::atoi(env);
         if (t >= 0 && t < kNumTiles) return t;
     }
+    if (Nout >= K) return 0;
     const long long tiles = (long long)N * ((C + 127) / 128) * ((Nout + 191) / 192);
-    return tiles <= 256 ? 1 : 0;
+    return tiles <= 256 ? 1 : 2;
 }
 
 // ------------------------------------------------------------------------------------ fp32 / FMA
@@ -398,7 +432,7 @@ hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, 
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
     if (d.dtype == SMILE_DTYPE_BF16) {
         GemmArgs g{xe, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0};
-        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff), s, t0, t1);
+        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
     }
     if (t0 && t1) (void)hipEventRecord(t0, s);
     const hipError_t err = launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
@@ -414,7 +448,7 @@ hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws
     const int N = d.n_groups * d.m_local;
     if (d.dtype == SMILE_DTYPE_BF16) {
         GemmArgs g{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0};
-        return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model), s);
+        return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
     }
     return launch_f32(static_cast<const float *>(ws.hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,
