@@ -203,8 +203,8 @@ typedef struct smile_layer_io {
 /* The whole forward pass in one call: enqueues the six steps above in order on
  * `stream` (gate logits, route, dispatch, expert FFN, combine, loss).  Same checks
  * and bit-identical results as calling them one by one, with two kernel launches
- * fewer (the loss is produced by the routing scan kernel, and the last routing
- * step runs inside the dispatch kernel). */
+ * fewer (the last routing step and the loss both run inside the dispatch
+ * kernel). */
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
 
 #ifdef __cplusplus

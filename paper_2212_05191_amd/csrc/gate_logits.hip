@@ -3,11 +3,12 @@
 // skinny product [T,d] x [d,n+m].  n+m is 10-40 in the paper-shaped workloads, so the kernel is
 // bound by the single read of x from HBM; the weights (<= 80 KB) stay in L2.
 //
-// bf16: one workgroup of 4 waves owns 16 token rows; the waves split the K (d) range in 64-wide
-// chunks, each feeding v_mfma_f32_16x16x32_bf16 straight from global memory (a lane reads 32
-// contiguous bytes of its row, so 4 lanes cover a full 128-byte line), then the 4 partial
-// accumulators are summed through LDS in a fixed order.  16 rows per workgroup keeps >= 512
-// workgroups in flight for the smallest paper-shaped batch (T = 8192).
+// bf16: one workgroup of 4 waves owns RT x 16 token rows; the waves split the K (d) range in
+// 64-wide chunks, each feeding v_mfma_f32_16x16x32_bf16 straight from global memory (a lane reads
+// 32 contiguous bytes of its row, so 4 lanes cover a full 128-byte line), then the 4 partial
+// accumulators are summed through LDS in a fixed order.  Every workgroup re-reads the router
+// weights from L2, so RT grows with T (weight traffic / RT) while keeping >= 512 workgroups:
+// RT = 1 for the smallest paper-shaped batch (T = 8192), 4 from T = 32768.
 // fp32: plain FMA kernel, one thread per (token, column), 4 partial sums.
 #include "smile_internal.hpp"
 
@@ -21,18 +22,20 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 constexpr int kRows = 16;      // token rows per workgroup
 constexpr int kWaves = 4;      // K-split factor
 
-// CT = number of 16-column tiles covering the n+m logits columns.
-template <int CT>
+// CT = number of 16-column tiles covering the n+m logits columns; RT = 16-row tiles per workgroup.
+template <int CT, int RT>
 __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
     const __bf16 *__restrict__ x, const __bf16 *__restrict__ w_inter, const __bf16 *__restrict__ w_intra,
     float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m)
 {
-    __shared__ f32x4 red[kWaves - 1][CT][64];
+    __shared__ f32x4 red[kWaves - 1][RT][CT][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, kg = lane >> 4;
-    const int row0 = blockIdx.x * kRows;
-    const __bf16 *xrow = x + (size_t)min(row0 + r, T - 1) * d;
+    const int row0 = blockIdx.x * kRows * RT;
+    const __bf16 *xrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) xrow[rt] = x + (size_t)min(row0 + rt * kRows + r, T - 1) * d;
 
     // the weight row this lane feeds as the B operand of column tile ct (null: padding column)
     const __bf16 *wrow[CT];
@@ -42,9 +45,11 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
         wrow[ct] = c < n ? w_inter + (size_t)c * d : (c < n + m ? w_intra + (size_t)(c - n) * d : nullptr);
     }
 
-    f32x4 acc[CT];
+    f32x4 acc[RT][CT];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     const int chunks = d / 64;
@@ -53,39 +58,50 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
         // the contraction index may be visited in any order as long as A and B agree: lane group kg
         // takes k0 + kg*16 + [0,8) for the first MFMA and + [8,16) for the second
         const int k = (wave + it * kWaves) * 64 + kg * 16;
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(xrow + k);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(xrow + k + 8);
+        bf16x8 a0[RT], a1[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            a0[rt] = *reinterpret_cast<const bf16x8 *>(xrow[rt] + k);
+            a1[rt] = *reinterpret_cast<const bf16x8 *>(xrow[rt] + k + 8);
+        }
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             const bf16x8 b0 = wrow[ct] ? *reinterpret_cast<const bf16x8 *>(wrow[ct] + k) : zero;
             const bf16x8 b1 = wrow[ct] ? *reinterpret_cast<const bf16x8 *>(wrow[ct] + k + 8) : zero;
-            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b0, acc[ct], 0, 0, 0);
-            acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, acc[ct], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[rt], b0, acc[rt][ct], 0, 0, 0);
+                acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[rt], b1, acc[rt][ct], 0, 0, 0);
+            }
         }
     }
 
     if (wave > 0) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) red[wave - 1][ct][lane] = acc[ct];
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) red[wave - 1][rt][ct][lane] = acc[rt][ct];
     }
     __syncthreads();
     if (wave == 0) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            f32x4 s = acc[ct];
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int w = 0; w < kWaves - 1; ++w) s += red[w][ct][lane];
-            // accumulator element i of this lane is (row kg*4 + i, column r) of the 16x16 tile
-            const int c = ct * 16 + r;
+            for (int ct = 0; ct < CT; ++ct) {
+                f32x4 s = acc[rt][ct];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = row0 + kg * 4 + i;
-                if (row < T) {
-                    if (c < n) logits_inter[(size_t)row * n + c] = s[i];
-                    else if (c < n + m) logits_intra[(size_t)row * m + (c - n)] = s[i];
+                for (int w = 0; w < kWaves - 1; ++w) s += red[w][rt][ct][lane];
+                // accumulator element i of this lane is (row kg*4 + i, column r) of the 16x16 tile
+                const int c = ct * 16 + r;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = row0 + rt * kRows + kg * 4 + i;
+                    if (row < T) {
+                        if (c < n) logits_inter[(size_t)row * n + c] = s[i];
+                        else if (c < n + m) logits_intra[(size_t)row * m + (c - n)] = s[i];
+                    }
                 }
             }
-        }
     }
 }
 
@@ -106,15 +122,25 @@ __global__ __launch_bounds__(256) void gate_logits_f32_kernel(
     else logits_intra[(size_t)t * m + (c - n)] = v;
 }
 
+template <int CT, int RT>
+void launch_bf16_rt(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+                    float *logits_inter, float *logits_intra, hipStream_t s)
+{
+    const int blocks = (d.T + kRows * RT - 1) / (kRows * RT);
+    hipLaunchKernelGGL((gate_logits_bf16_kernel<CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
+                       static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
+                       static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
+                       d.n_groups, d.m_local);
+}
+
 template <int CT>
 void launch_bf16(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
                  float *logits_inter, float *logits_intra, hipStream_t s)
 {
-    const int blocks = (d.T + kRows - 1) / kRows;
-    hipLaunchKernelGGL(gate_logits_bf16_kernel<CT>, dim3(blocks), dim3(64 * kWaves), 0, s,
-                       static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
-                       static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
-                       d.n_groups, d.m_local);
+    // the accumulators of RT x CT tiles must stay in registers: RT * CT <= 16
+    if (d.T >= 32768 && CT <= 4) launch_bf16_rt<CT, 4>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
+    else if (d.T >= 16384) launch_bf16_rt<CT, 2>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
+    else launch_bf16_rt<CT, 1>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
 }
 
 }  // namespace

@@ -53,8 +53,11 @@ __global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
     const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
     const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
     int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, u32x4 *__restrict__ xe,
-    long long total, int ppr, int n, int m, int C)
+    long long total, int ppr, int n, int m, int C, LossArgs loss, int T, float alpha, float beta)
 {
+    // Eq. 4 from the (complete) routing statistics, by the first wave of the last workgroup
+    if (loss.out3 && blockIdx.x == gridDim.x - 1 && threadIdx.x < 64)
+        aux_loss_wave(loss.group_count, loss.local_count, loss.p_sum, loss.q_sum, T, n, m, alpha, beta, loss.out3);
     const long long stride = (long long)gridDim.x * kThreads;
     long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
     const int N = n * m;
@@ -166,7 +169,7 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
 
 hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
-                                    int32_t *slot, void *xe, hipStream_t s)
+                                    int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s)
 {
     const int esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
     const int ppr = d.d_model * esz / 16;
@@ -174,7 +177,7 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
     hipLaunchKernelGGL(dispatch_finalize_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
                        static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist, ws.block_group_hist,
                        ws.rank_in_block, ws.pos_in_block, pos_in_group, slot, static_cast<u32x4 *>(xe), total, ppr,
-                       d.n_groups, d.m_local, d.capacity);
+                       d.n_groups, d.m_local, d.capacity, loss, d.T, d.alpha, d.beta);
     return hipGetLastError();
 }
 

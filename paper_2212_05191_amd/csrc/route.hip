@@ -6,9 +6,9 @@
 //                  column sums of p and q; the token's rank among EARLIER tokens of the same block
 //                  with the same group / the same expert (wave64 ballots + LDS counters); per-block
 //                  histograms.
-//   route_scan     one workgroup: exclusive scan of the block histograms along the block axis (turning
-//                  them into block offsets; one wave per column, 64 blocks per shuffle scan), totals,
-//                  kept counts, and the fixed-order sums of p and q.
+//   route_scan     one wave per histogram column: exclusive scan along the block axis (turning the
+//                  histograms into block offsets; 64 blocks per shuffle scan), totals, kept counts,
+//                  and the fixed-order sums of p and q.
 //   route_finalize one thread per token: global rank = block offset + in-block rank; capacity cut.
 //                  (The chained forward pass skips this kernel and does the same inside dispatch.)
 //
@@ -156,6 +156,12 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     }
     for (int i = tid; i < N; i += kRouteBlock) block_expert_hist[(size_t)b * N + i] = hist[i];
     for (int i = tid; i < n; i += kRouteBlock) block_group_hist[(size_t)b * n + i] = ghist[i];
+    // per-block counts by local index (summed over groups), stored behind the [B][n] group histograms
+    for (int j = tid; j < m; j += kRouteBlock) {
+        int c = 0;
+        for (int i = 0; i < n; ++i) c += hist[i * m + j];
+        block_group_hist[(size_t)gridDim.x * n + (size_t)b * m + j] = c;
+    }
 
     block_column_sums(rp, bias_inter, n, mx_p, iz_p, valid, tile, part, block_p_sum + (size_t)b * n);
     block_column_sums(rq, bq, m, mx_q, iz_q, valid, tile, part, block_q_sum + (size_t)b * m);
@@ -193,52 +199,47 @@ __device__ __forceinline__ float wave_sum_column(const float *__restrict__ part,
     return s;
 }
 
-// One workgroup of 16 waves; each wave takes columns wave, wave+16, ... of the work list
-// [N expert columns | n group columns | n p-sum columns | m q-sum columns].
-__global__ __launch_bounds__(1024) void route_scan_kernel(
+// One wave per column of the work list
+//   [N expert columns | n group columns | n p-sum columns | m q-sum columns | m local-count columns],
+// 4 waves per workgroup; the columns are independent, so the grid spreads them over the chip.
+constexpr int kScanWaves = 4;
+
+__global__ __launch_bounds__(64 * kScanWaves) void route_scan_kernel(
     int B, int n, int m, int C,
     int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ block_group_hist,
     const float *__restrict__ block_p_sum, const float *__restrict__ block_q_sum,
     int32_t *__restrict__ group_count, int32_t *__restrict__ local_count,
     int32_t *__restrict__ expert_count, int32_t *__restrict__ kept_count,
-    float *__restrict__ p_sum, float *__restrict__ q_sum,
-    int T, float alpha, float beta, float *__restrict__ loss3)
+    float *__restrict__ p_sum, float *__restrict__ q_sum)
 {
-    extern __shared__ int32_t ecnt[];   // [N] expert totals, [n] group totals, [m] local totals, then float [n], [m]
     const int N = n * m;
-    int32_t *gcnt = ecnt + N, *lcnt = gcnt + n;
-    float *psum = reinterpret_cast<float *>(lcnt + m), *qsum = psum + n;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, waves = blockDim.x >> 6;
-    const int work = N + 2 * n + m;
-    for (int w = wave; w < work; w += waves) {
-        if (w < N) {
-            const int total = wave_scan_column(block_expert_hist, B, N, w);
-            if (lane == 0) {
-                ecnt[w] = total;
-                expert_count[w] = total;
-                kept_count[w] = min(total, C);
-            }
-        } else if (w < N + n) {
-            const int total = wave_scan_column(block_group_hist, B, n, w - N);
-            if (lane == 0) { gcnt[w - N] = total; group_count[w - N] = total; }
-        } else if (w < N + 2 * n) {
-            const float s = wave_sum_column(block_p_sum, B, n, w - N - n);
-            if (lane == 0) { psum[w - N - n] = s; p_sum[w - N - n] = s; }
-        } else {
-            const float s = wave_sum_column(block_q_sum, B, m, w - N - 2 * n);
-            if (lane == 0) { qsum[w - N - 2 * n] = s; q_sum[w - N - 2 * n] = s; }
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * kScanWaves + (threadIdx.x >> 6);
+    if (w < N) {
+        const int total = wave_scan_column(block_expert_hist, B, N, w);
+        if (lane == 0) {
+            expert_count[w] = total;
+            kept_count[w] = min(total, C);
         }
-    }
-    __syncthreads();
-    for (int j = tid; j < m; j += blockDim.x) {
+    } else if (w < N + n) {
+        const int total = wave_scan_column(block_group_hist, B, n, w - N);
+        if (lane == 0) group_count[w - N] = total;
+    } else if (w < N + 2 * n) {
+        const float s = wave_sum_column(block_p_sum, B, n, w - N - n);
+        if (lane == 0) p_sum[w - N - n] = s;
+    } else if (w < N + 2 * n + m) {
+        const float s = wave_sum_column(block_q_sum, B, m, w - N - 2 * n);
+        if (lane == 0) q_sum[w - N - 2 * n] = s;
+    } else if (w < N + 2 * n + 2 * m) {
+        // local_count[j] = tokens whose local index is j, over all groups.  The expert columns are
+        // being rewritten by other waves, so it is summed from the per-block counts by local index
+        // that route_decide stored behind the group histograms.
+        const int j = w - N - 2 * n - m;
         int s = 0;
-        for (int i = 0; i < n; ++i) s += ecnt[i * m + j];
-        lcnt[j] = s;
-        local_count[j] = s;
-    }
-    if (loss3) {   // Eq. 4 right here saves the separate loss launch of the chained forward pass
-        __syncthreads();
-        if (wave == 0) aux_loss_wave(gcnt, lcnt, psum, qsum, T, n, m, alpha, beta, loss3);
+        for (int b = lane; b < B; b += 64) s += block_group_hist[(size_t)B * n + (size_t)b * m + j];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) local_count[j] = s;
     }
 }
 
@@ -273,7 +274,7 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
                         int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
-                        bool finalize, float *loss3)
+                        bool finalize)
 {
     const int n = d.n_groups, m = d.m_local, N = n * m;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
@@ -284,10 +285,10 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                        ws.block_group_hist, ws.block_p_sum, ws.block_q_sum);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), sizeof(int32_t) * (size_t)(N + 2 * n + 2 * m), s, B,
-                       n, m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
-                       group_count, local_count, expert_count, kept_count, p_sum, q_sum, d.T, d.alpha, d.beta,
-                       loss3);
+    const int columns = N + 2 * n + 2 * m;
+    hipLaunchKernelGGL(route_scan_kernel, dim3((columns + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0, s, B, n,
+                       m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
+                       group_count, local_count, expert_count, kept_count, p_sum, q_sum);
     err = hipGetLastError();
     if (err != hipSuccess || !finalize) return err;
     hipLaunchKernelGGL(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,

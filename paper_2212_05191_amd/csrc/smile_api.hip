@@ -19,7 +19,7 @@ Layout workspace_layout(const smile_layer_desc &d)
     size_t off = 0;
     L.route_blocks = (int32_t)B;
     L.off_block_expert_hist = off; off = align_up(off + B * N * sizeof(int32_t), 256);
-    L.off_block_group_hist = off;  off = align_up(off + B * d.n_groups * sizeof(int32_t), 256);
+    L.off_block_group_hist = off;  off = align_up(off + B * (d.n_groups + d.m_local) * sizeof(int32_t), 256);
     L.off_block_p_sum = off;       off = align_up(off + B * d.n_groups * sizeof(float), 256);
     L.off_block_q_sum = off;       off = align_up(off + B * d.m_local * sizeof(float), 256);
     L.off_rank_in_block = off;     off = align_up(off + (size_t)d.T * sizeof(int32_t), 256);
@@ -259,9 +259,8 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         return SMILE_INVALID_ARG;
     if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
     if ((io->prof_up_start == nullptr) != (io->prof_up_stop == nullptr)) return SMILE_INVALID_ARG;
-    // Same kernels as the step-by-step calls, with two launches saved: the loss comes out of the
-    // routing scan kernel and the last routing step (block offset + rank, capacity cut) runs
-    // inside the dispatch kernel.
+    // Same kernels as the step-by-step calls, with two launches saved: the last routing step (block
+    // offset + rank, capacity cut) and the loss both run inside the dispatch kernel.
     const smile_layer_desc &d = ctx->desc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err = launch_gate_logits(d, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, s);
@@ -269,10 +268,11 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         err = launch_route(d, ctx->ws, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
                            io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top, io->q_top,
                            io->group_count, io->local_count, io->expert_count, io->kept_count, io->p_sum, io->q_sum,
-                           s, /*finalize=*/false, io->loss3);
+                           s, /*finalize=*/false);
     if (err == hipSuccess)
         err = launch_dispatch_finalize(d, ctx->ws, io->x, io->group_idx, io->local_idx, io->pos_in_group, io->slot,
-                                       io->xe, s);
+                                       io->xe, LossArgs{io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3},
+                                       s);
     if (err == hipSuccess)
         err = launch_expert_ffn_up(d, ctx->ws, io->xe, io->kept_count, io->w1, io->b1, s,
                                    static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop));

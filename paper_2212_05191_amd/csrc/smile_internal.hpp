@@ -15,7 +15,7 @@ constexpr int kRouteBlock = 256;
 struct Workspace {
     // routing: per-block histograms turned into exclusive block offsets by the scan kernel
     int32_t *block_expert_hist;   // [B][N]
-    int32_t *block_group_hist;    // [B][n]
+    int32_t *block_group_hist;    // [B][n] per group, then [B][m] per local index
     float *block_p_sum;           // [B][n]
     float *block_q_sum;           // [B][m]
     int32_t *rank_in_block;       // [T] rank among earlier tokens of the same block with the same expert
@@ -74,22 +74,28 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
                               float *logits_inter, float *logits_intra, hipStream_t s);
 
 // finalize = false leaves pos_in_group / slot unwritten (the block-local ranks stay in the workspace
-// for launch_dispatch_finalize); loss3 != nullptr also writes the Eq. 4 loss from the scan kernel.
+// for launch_dispatch_finalize).
 hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const float *logits_inter,
                         const float *logits_intra, const float *bias_inter, const float *bias_intra,
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
                         int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
-                        bool finalize = true, float *loss3 = nullptr);
+                        bool finalize = true);
 
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s);
 
 // dispatch fused with the last routing step: computes pos_in_group / slot from the workspace ranks
-// and block offsets, writes them, and moves the rows
+// and block offsets, writes them, and moves the rows; loss != nullptr: one wave also evaluates Eq. 4
+// from the routing statistics (saves the separate loss launch)
+struct LossArgs {
+    const int32_t *group_count, *local_count;
+    const float *p_sum, *q_sum;
+    float *out3;   // null: no loss
+};
 hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
-                                    int32_t *slot, void *xe, hipStream_t s);
+                                    int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s);
 
 hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
                           const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s);
