@@ -183,6 +183,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
         if (s < slabs) issue(s, s);
 
     int stage = 0;
+    const bool wave_live = rt * BM + wm * WM < rows;   // wave-uniform
     // One K slab.  ISSUE: this iteration also issues the loads of slab kt+STAGES-1 (always true in
     // the steady state, false in the last STAGES-1 iterations).  The loads are spread over the
     // k-steps and the instruction order is pinned (sched_group_barrier: one MFMA, one LDS read, ...,
@@ -211,12 +212,17 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
             for (int i = 0; i < TN; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, cur[wbase + i * 32 * PPR + p]);
         };
         constexpr int KS = BK / 16;
+        if (!wave_live) {
+            // none of this wave's token rows exists (ragged tile): it only helps loading
+            if (ISSUE) issue(nxt, nstage);
+            stage = stage + 1 == STAGES ? 0 : stage + 1;
+            return;
+        }
         fetch(0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
             // this k-step's share of the next slab's load instructions
-            constexpr int dummy = 0; (void)dummy;
             const int l0 = GPW * kk / KS, l1 = GPW * (kk + 1) / KS;
             if (kk + 1 < KS) fetch((kk + 1) & 1, kk + 1);
             if (ISSUE) {
