@@ -37,7 +37,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", help="one of cfg1..cfg5 (cfg2 is the headline workload)")
+    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload) or t2_48b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reads 256 MiB, writes 256 MiB) so that a "
@@ -57,7 +57,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     lib = B.load()
-    cfg = wl.CONFIGS[args.workload]
+    cfg = wl.get_config(args.workload)
     layer = GpuLayer(cfg, workers=16)
     b, h = layer.buf, layer.ctx.handle
     stream = torch.cuda.current_stream().cuda_stream

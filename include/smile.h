@@ -27,9 +27,9 @@
  *     weights, the expert buffers and y: 0 = fp32, 1 = bfloat16.  Logits,
  *     probabilities, gates and the loss are always fp32.
  *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for bf16:
- *     d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096,
- *     n + m <= 128 for smile_gate_logits; N*C*max(d,F) < 2^40 elements;
- *     N*C and T below 2^31.
+ *     d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096;
+ *     N*C*max(d,F) < 2^40 elements; N*C and T below 2^31.  n = 1 (or m = 1)
+ *     gives the flat one-level top-1 router of Section 2 (Eq. 1-2, k = 1).
  *   - Floating-point inputs must be finite; NaN/Inf give unspecified results.
  */
 #ifndef SMILE_H

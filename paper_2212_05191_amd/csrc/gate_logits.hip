@@ -1,6 +1,7 @@
 // Router logits r(x) = W_r x (Section 2, text before Eq. 1) for the inter router W_p[n,d] and the
 // intra router W_q[m,d] (Section 3.2.1: two tied routers reading the same token), computed as one
-// skinny product [T,d] x [d,n+m].  n+m is 10-40 in the paper-shaped workloads, so the kernel is
+// skinny product [T,d] x [d,n+m].  n+m is 10-40 in the paper-shaped workloads (up to 257 for the flat
+// one-level router the paper compares against), so the kernel is
 // bound by the single read of x from HBM; the weights (<= 80 KB) stay in L2.
 //
 // bf16: one workgroup of 4 waves owns RT x 16 token rows; the waves split the K (d) range in
@@ -10,6 +11,8 @@
 // weights from L2, so RT grows with T (weight traffic / RT) while keeping >= 512 workgroups:
 // RT = 1 for the smallest paper-shaped batch (T = 8192), 4 from T = 32768.
 // fp32: plain FMA kernel, one thread per (token, column), 4 partial sums.
+#include <algorithm>
+
 #include "smile_internal.hpp"
 
 namespace smile {
@@ -26,7 +29,7 @@ constexpr int kWaves = 4;      // K-split factor
 template <int CT, int RT>
 __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
     const __bf16 *__restrict__ x, const __bf16 *__restrict__ w_inter, const __bf16 *__restrict__ w_intra,
-    float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m)
+    float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m, int col0)
 {
     __shared__ f32x4 red[kWaves - 1][RT][CT][64];
 
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
     const __bf16 *wrow[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-        const int c = ct * 16 + r;
+        const int c = col0 + ct * 16 + r;
         wrow[ct] = c < n ? w_inter + (size_t)c * d : (c < n + m ? w_intra + (size_t)(c - n) * d : nullptr);
     }
 
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
 #pragma unroll
                 for (int w = 0; w < kWaves - 1; ++w) s += red[w][rt][ct][lane];
                 // accumulator element i of this lane is (row kg*4 + i, column r) of the 16x16 tile
-                const int c = ct * 16 + r;
+                const int c = col0 + ct * 16 + r;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int row = row0 + rt * kRows + kg * 4 + i;
@@ -124,23 +127,24 @@ __global__ __launch_bounds__(256) void gate_logits_f32_kernel(
 
 template <int CT, int RT>
 void launch_bf16_rt(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
-                    float *logits_inter, float *logits_intra, hipStream_t s)
+                    float *logits_inter, float *logits_intra, int col0, hipStream_t s)
 {
     const int blocks = (d.T + kRows * RT - 1) / (kRows * RT);
     hipLaunchKernelGGL((gate_logits_bf16_kernel<CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
                        static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
                        static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
-                       d.n_groups, d.m_local);
+                       d.n_groups, d.m_local, col0);
 }
 
+// columns [col0, col0 + 16*CT)
 template <int CT>
 void launch_bf16(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
-                 float *logits_inter, float *logits_intra, hipStream_t s)
+                 float *logits_inter, float *logits_intra, int col0, hipStream_t s)
 {
     // the accumulators of RT x CT tiles must stay in registers: RT * CT <= 16
-    if (d.T >= 32768 && CT <= 4) launch_bf16_rt<CT, 4>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
-    else if (d.T >= 16384) launch_bf16_rt<CT, 2>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
-    else launch_bf16_rt<CT, 1>(d, x, w_inter, w_intra, logits_inter, logits_intra, s);
+    if (d.T >= 32768 && CT <= 4) launch_bf16_rt<CT, 4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
+    else if (d.T >= 16384) launch_bf16_rt<CT, 2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
+    else launch_bf16_rt<CT, 1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
 }
 
 }  // namespace
@@ -150,16 +154,19 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
 {
     const int cols = d.n_groups + d.m_local;
     if (d.dtype == SMILE_DTYPE_BF16) {
-        switch ((cols + 15) / 16) {
-        case 1: launch_bf16<1>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 2: launch_bf16<2>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 3: launch_bf16<3>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 4: launch_bf16<4>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 5: launch_bf16<5>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 6: launch_bf16<6>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 7: launch_bf16<7>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        case 8: launch_bf16<8>(d, x, w_inter, w_intra, logits_inter, logits_intra, s); break;
-        default: return hipErrorInvalidValue;
+        // up to 128 columns per pass over x (8 accumulator tiles); wider routers (a flat one-level
+        // router over all N experts) take several passes
+        for (int col0 = 0; col0 < cols; col0 += 128) {
+            switch ((std::min(cols - col0, 128) + 15) / 16) {
+            case 1: launch_bf16<1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 2: launch_bf16<2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 3: launch_bf16<3>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 4: launch_bf16<4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 5: launch_bf16<5>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 6: launch_bf16<6>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 7: launch_bf16<7>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            default: launch_bf16<8>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            }
         }
     } else {
         const long long total = (long long)d.T * cols;

@@ -163,7 +163,6 @@ smile_status smile_gate_logits(smile_ctx *ctx, const void *x, const void *w_inte
 {
     if (!ctx || bad(x) || bad(w_inter) || bad(w_intra) || bad(logits_inter) || bad(logits_intra))
         return SMILE_INVALID_ARG;
-    if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
     return from_hip(launch_gate_logits(ctx->desc, x, w_inter, w_intra, logits_inter, logits_intra,
                                        static_cast<hipStream_t>(stream)));
 }
@@ -257,7 +256,6 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         bad(io->local_count) || bad(io->expert_count) || bad(io->kept_count) || bad(io->p_sum) ||
         bad(io->q_sum) || bad(io->xe) || bad(io->ye) || bad(io->y) || bad(io->loss3))
         return SMILE_INVALID_ARG;
-    if (ctx->desc.n_groups + ctx->desc.m_local > 128) return SMILE_UNSUPPORTED;
     if ((io->prof_up_start == nullptr) != (io->prof_up_stop == nullptr)) return SMILE_INVALID_ARG;
     // Same kernels as the step-by-step calls, with two launches saved: the last routing step (block
     // offset + rank, capacity cut) and the loss both run inside the dispatch kernel.

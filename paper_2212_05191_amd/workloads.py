@@ -60,6 +60,21 @@ CONFIGS = {
 }
 
 
+# Further paper-shaped workloads (not part of the five benchmark configurations): the largest model of
+# Table 2 (hidden 1600, intermediate 6400, micro-batch 64 x sequence 128 = 8192 tokens per GPU) with the
+# capacity factor 2.0 of Section 4.2; 16 resident experts as in cfg2.
+EXTRA_CONFIGS = {
+    "t2_48b": LayerConfig("t2_48b", 8192, 1600, 6400, 2, 8, 2.0, 1024, "bf16", "gelu", seed=6),
+    # cfg4 with the flat one-level router the paper compares against (Switch Transformer: Section 2,
+    # Eq. 1-2 with k = 1): same tokens, experts and capacity, one 128-way gate instead of 16 x 8
+    "cfg4_flat": LayerConfig("cfg4_flat", 32768, 768, 3072, 1, 128, 1.0, 256, "bf16", "gelu", seed=4),
+}
+
+
+def get_config(name: str) -> LayerConfig:
+    return CONFIGS[name] if name in CONFIGS else EXTRA_CONFIGS[name]
+
+
 def _rng(seed: int, tid: int, sub: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) | int(tid), int(sub)]))
 

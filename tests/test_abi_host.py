@@ -99,19 +99,19 @@ def test_workspace_size_and_alignment_checks():
 
 def test_entry_points_reject_bad_pointers_before_any_launch():
     lib = B.load()
-    d = _desc(n_groups=100, m_local=40)      # n+m > 128: gate kernel does not cover it
+    d = _desc(n_groups=100, m_local=40)
     need = B.smile_workspace_bytes(d)
     h = C.c_void_p(None)
     fake = 0x7F0000000000
     assert lib.smile_create_with_workspace(C.byref(d), fake, need, C.byref(h)) == B.OK
-    p = fake + 4096          # aligned dummy pointer; checks must fail before it could be used
+    p = fake + 4096          # aligned dummy pointer; every call below has a bad argument, so the checks
+                             # fail before anything could be enqueued with it
     try:
         # NULL ctx
         assert lib.smile_gate_logits(None, p, p, p, p, p, None) == B.INVALID_ARG
         # NULL and misaligned tensors
         assert lib.smile_gate_logits(h, None, p, p, p, p, None) == B.INVALID_ARG
         assert lib.smile_gate_logits(h, p, p, p, p + 4, p, None) == B.INVALID_ARG
-        assert lib.smile_gate_logits(h, p, p, p, p, p, None) == B.UNSUPPORTED
         args = [p] * 17
         for i in [0, 1, 4, 7, 16]:
             bad = list(args)
@@ -132,7 +132,9 @@ def test_entry_points_reject_bad_pointers_before_any_launch():
         io.y = None
         assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
         io.y = p
-        assert lib.smile_layer_forward(h, C.byref(io), None) == B.UNSUPPORTED   # n+m > 128, nothing enqueued
+        io.prof_up_stop = None      # timing events come as a pair or not at all
+        assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_up_timed(h, p, p, p, None, p, None, None) == B.INVALID_ARG
     finally:
         assert lib.smile_destroy(h) == B.OK
 

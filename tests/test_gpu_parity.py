@@ -60,6 +60,9 @@ SMALL = [
     wl.small_config("single_local", 600, 64, 128, 6, 1, 80, "f32", "gelu", seed=18),
     wl.small_config("one_expert_dense", 200, 128, 256, 1, 1, 200, "bf16", "gelu", seed=19),
     wl.small_config("many_groups", 5000, 64, 64, 40, 24, 9, "bf16", "relu", seed=20),
+    # flat one-level routers (Section 2, Eq. 1-2 with k = 1): more than 128 logit columns -> two gate passes
+    wl.small_config("flat_switch_200", 6000, 128, 128, 1, 200, 40, "bf16", "gelu", seed=24),
+    wl.small_config("flat_switch_t_130", 3000, 64, 64, 130, 1, 30, "bf16", "relu", seed=25),
 ]
 
 
@@ -150,9 +153,9 @@ def test_cfg2_full_parity(torch_cuda):
         layer.close()
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5", "t2_48b"])
 def test_full_size_configs_sampled_parity(torch_cuda, name):
-    cfg = wl.CONFIGS[name]
+    cfg = wl.get_config(name)
     layer = _run(cfg, "chained", workers=16)
     try:
         info = parity.check_sampled(cfg, layer)

@@ -29,7 +29,7 @@ def _rand_logits(rng, T, n, m, scale=1.0):
 
 def test_capacity_of_the_five_configs():
     # C = ceil(cf*T/N) (Section 4.2 "capacity factor", Switch-style): exact integers for the benchmark configs
-    for cfg in wl.CONFIGS.values():
+    for cfg in list(wl.CONFIGS.values()) + list(wl.EXTRA_CONFIGS.values()):
         assert oracle.capacity(cfg.T, cfg.N, cfg.capacity_factor) == cfg.capacity
     assert oracle.capacity(10, 4, 1.0) == 3      # ceil(2.5)
     assert oracle.capacity(1, 64, 1.0) == 1      # never below one row
