@@ -98,7 +98,7 @@ def main():
         assert hip.hipEventElapsedTime(ctypes.byref(ms), a, z) == 0
         return float(ms.value)
 
-    io = layer.io
+    io = layer.io_fused     # no expert buffers: dispatch / combine fused into the expert GEMMs
 
     def step(ev=None):
         """One forward pass through the single chained entry point (all steps, fewest launches)."""

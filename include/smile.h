@@ -193,7 +193,8 @@ typedef struct smile_layer_io {
     float *gate, *p_top, *q_top;
     int32_t *group_count, *local_count, *expert_count, *kept_count;
     float *p_sum, *q_sum;
-    void *xe, *ye, *y;
+    void *xe, *ye;   /* expert buffers [N,C,d]: both given, or both NULL (see smile_layer_forward) */
+    void *y;
     float *loss3;
     /* optional: hipEvent_t pair (both or neither) receiving the begin / end timestamps of the
      * up-projection kernel, as in smile_expert_ffn_up_timed; NULL = no timing */
@@ -202,9 +203,14 @@ typedef struct smile_layer_io {
 
 /* The whole forward pass in one call: enqueues the six steps above in order on
  * `stream` (gate logits, route, dispatch, expert FFN, combine, loss).  Same checks
- * and bit-identical results as calling them one by one, with two kernel launches
- * fewer (the last routing step and the loss both run inside the dispatch
- * kernel). */
+ * and bit-identical results as calling them one by one, with fewer launches:
+ *   - io->xe and io->ye given: the expert buffers are materialised as by
+ *     smile_dispatch / smile_expert_ffn; the last routing step and the loss run
+ *     inside the dispatch kernel (7 launches instead of 9);
+ *   - io->xe == io->ye == NULL: the permutations are fused into the expert GEMMs --
+ *     the up-projection gathers its rows from x through a slot -> token map and the
+ *     down-projection returns gate-weighted rows straight to y; rows of dropped
+ *     tokens are zeroed by the routing (6 launches, no [N,C,d] traffic). */
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
 
 #ifdef __cplusplus

@@ -78,14 +78,37 @@ __device__ __forceinline__ float activate(float v)
 // ------------------------------------------------------------------------------------ bf16 / MFMA
 
 struct GemmArgs {
-    const void *x;          // [N][C][K]
+    const void *x;          // [N][C][K]; with x_rows: the token matrix [T][K]
     const void *w;          // [N][Nout][K]
     const void *bias;       // [N][Nout] or null
-    void *y;                // [N][C][Nout]
+    void *y;                // [N][C][Nout], or null when only the scattered output is wanted
     const int32_t *kept;    // [N]
     int C, Nout, K;
     int row_tiles, col_tiles, tiles;   // tiles = N*row_tiles*col_tiles
+    // Permutation fused into the GEMM (both optional, [N][C] token index of each buffer row):
+    const int32_t *x_rows;  // gather: input row r of expert e is x[x_rows[e*C + r]]  (dispatch fused in)
+    const int32_t *y_rows;  // scatter: output row also goes to y_tok[y_rows[e*C + r]] * gate  (combine fused in)
+    void *y_tok;            // [T][Nout]
+    const float *gate;      // [T]
 };
+
+// One 16-byte piece (8 bf16) times a gate: fp32 product, rounded to bf16 (nearest even) -- the same
+// arithmetic as the stand-alone combine kernel.
+__device__ __forceinline__ u32x4 scale_bf16x8(u32x4 v, float g)
+{
+    u32x4 r;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float lo = __uint_as_float(v[k] << 16) * g;
+        const float hi = __uint_as_float(v[k] & 0xffff0000u) * g;
+        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+        bf16x2 pk;
+        pk[0] = (__bf16)lo;
+        pk[1] = (__bf16)hi;
+        r[k] = __builtin_bit_cast(uint32_t, pk);
+    }
+    return r;
+}
 
 #define SMILE_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define SMILE_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -140,8 +163,9 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     if (rt * BM >= rows) return;
 
     const int K = a.K, Nout = a.Nout;
-    const __bf16 *X = static_cast<const __bf16 *>(a.x) + (size_t)e * a.C * K;
+    const __bf16 *X = static_cast<const __bf16 *>(a.x) + (a.x_rows ? (size_t)0 : (size_t)e * a.C * K);
     const __bf16 *W = static_cast<const __bf16 *>(a.w) + (size_t)e * Nout * K;
+    const int32_t *x_rows = a.x_rows ? a.x_rows + (size_t)e * a.C : nullptr;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -155,8 +179,12 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
         const int row = (wave + i * NW) * RPI + lr;            // row of the stage
         const int piece = lp ^ swz<BK, SWZ>(row);
         // rows past the end of the expert's tokens / of the weight matrix re-read the last valid one
-        src[i] = row < BM ? X + (size_t)min(rt * BM + row, rows - 1) * K + piece * 8
-                          : W + (size_t)min(ct * BN + row - BM, Nout - 1) * K + piece * 8;
+        if (row < BM) {
+            const int xr = min(rt * BM + row, rows - 1);
+            src[i] = X + (size_t)(x_rows ? x_rows[xr] : xr) * K + piece * 8;
+        } else {
+            src[i] = W + (size_t)min(ct * BN + row - BM, Nout - 1) * K + piece * 8;
+        }
     }
     auto issue = [&](int slab, int stage) {
 #pragma unroll
@@ -257,7 +285,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     // row lane%32) of its 32x32 tile.  One pass per 32-row slice of the wave tiles: bias +
     // activation + rounding, 8-byte writes into a [OROWS][BN] staging tile, then row-contiguous
     // 16-byte global stores by the whole workgroup.
-    __bf16 *Y = static_cast<__bf16 *>(a.y) + (size_t)e * a.C * Nout;
+    __bf16 *Y = a.y ? static_cast<__bf16 *>(a.y) + (size_t)e * a.C * Nout : nullptr;
+    const int32_t *y_rows = a.y_rows ? a.y_rows + (size_t)e * a.C : nullptr;
     const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (size_t)e * Nout : nullptr;
     u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
     constexpr int OPR = BN / 8;   // 16-byte pieces per output row
@@ -286,8 +315,15 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
             const int orow = id / OPR, piece = id - orow * OPR;
             const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
             const int col = ct * BN + piece * 8;
-            if (row < rows && col < Nout)
-                *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = lds[orow * OSTRIDE + piece];
+            if (row < rows && col < Nout) {
+                const u32x4 v = lds[orow * OSTRIDE + piece];
+                if (Y) *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = v;
+                if (y_rows) {   // gate-weighted return to token order (Eq. 3), fused
+                    const int tok = y_rows[row];
+                    *reinterpret_cast<u32x4 *>(static_cast<__bf16 *>(a.y_tok) + (size_t)tok * Nout + col) =
+                        scale_bf16x8(v, a.gate[tok]);
+                }
+            }
         }
     }
 }
@@ -356,7 +392,9 @@ int pick_tile(int N, int C, int Nout, int K)
 template <int ACT>
 __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
     const float *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias,
-    float *__restrict__ y, const int32_t *__restrict__ kept, int C, int Nout, int K, int row_tiles, int col_tiles)
+    float *__restrict__ y, const int32_t *__restrict__ kept, int C, int Nout, int K, int row_tiles, int col_tiles,
+    const int32_t *__restrict__ x_rows, const int32_t *__restrict__ y_rows, float *__restrict__ y_tok,
+    const float *__restrict__ gate)
 {
     constexpr int BT = 64, BK = 16;
     __shared__ float xs[BK][BT + 4];
@@ -369,11 +407,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
     const int rows = min(kept[e], C);
     if (rt * BT >= rows) return;
 
-    const float *X = x + (size_t)e * C * K;
+    const float *X = x + (x_rows ? (size_t)0 : (size_t)e * C * K);
     const float *W = w + (size_t)e * Nout * K;
     const int tid = threadIdx.x;
     const int lr = tid >> 2, lk = (tid & 3) * 4;            // loader: row lr, 4 floats at k offset lk
-    const int xrow = min(rt * BT + lr, rows - 1), wrow = min(ct * BT + lr, Nout - 1);
+    const int xr = min(rt * BT + lr, rows - 1);
+    const int xrow = x_rows ? x_rows[(size_t)e * C + xr] : xr, wrow = min(ct * BT + lr, Nout - 1);
     const int ty = tid >> 4, tx = tid & 15;                  // compute: rows ty*4.., cols tx*4..
 
     float acc[4][4] = {};
@@ -398,33 +437,41 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
         }
         __syncthreads();
     }
-    float *Y = y + (size_t)e * C * Nout;
+    float *Y = y ? y + (size_t)e * C * Nout : nullptr;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = rt * BT + ty * 4 + i;
         if (row >= rows) continue;
+        const int tok = y_rows ? y_rows[(size_t)e * C + row] : 0;
+        const float g = y_rows ? gate[tok] : 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int col = ct * BT + tx * 4 + j;
             if (col >= Nout) continue;
             float f = acc[i][j];
             if (bias) f += bias[(size_t)e * Nout + col];
-            Y[(size_t)row * Nout + col] = activate<ACT>(f);
+            f = activate<ACT>(f);
+            if (Y) Y[(size_t)row * Nout + col] = f;
+            if (y_rows) y_tok[(size_t)tok * Nout + col] = f * g;
         }
     }
 }
 
 hipError_t launch_f32(const float *x, const float *w, const float *bias, float *y, const int32_t *kept, int N,
-                      int C, int Nout, int K, int act, hipStream_t s)
+                      int C, int Nout, int K, int act, hipStream_t s, const int32_t *x_rows = nullptr,
+                      const int32_t *y_rows = nullptr, float *y_tok = nullptr, const float *gate = nullptr)
 {
     const int row_tiles = (C + 63) / 64, col_tiles = (Nout + 63) / 64;
     const dim3 grid(N * row_tiles * col_tiles), block(256);
     if (act == 0)
-        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<0>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles);
+        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<0>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
+                           x_rows, y_rows, y_tok, gate);
     else if (act == 1)
-        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<1>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles);
+        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<1>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
+                           x_rows, y_rows, y_tok, gate);
     else
-        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<2>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles);
+        hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<2>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
+                           x_rows, y_rows, y_tok, gate);
     return hipGetLastError();
 }
 
@@ -432,33 +479,39 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
-                                hipEvent_t t0, hipEvent_t t1)
+                                hipEvent_t t0, hipEvent_t t1, const void *x_tokens)
 {
     const int N = d.n_groups * d.m_local;
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
+    // x_tokens: read the rows straight from the token matrix through the slot -> token map
+    const int32_t *x_rows = x_tokens ? ws.slot_token : nullptr;
+    const void *src = x_tokens ? x_tokens : xe;
     if (d.dtype == SMILE_DTYPE_BF16) {
-        GemmArgs g{xe, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0};
+        GemmArgs g{src, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0, x_rows, nullptr, nullptr, nullptr};
         return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
     }
     if (t0 && t1) (void)hipEventRecord(t0, s);
-    const hipError_t err = launch_f32(static_cast<const float *>(xe), static_cast<const float *>(w1),
+    const hipError_t err = launch_f32(static_cast<const float *>(src), static_cast<const float *>(w1),
                                       static_cast<const float *>(b1), static_cast<float *>(ws.hidden), kept_count, N,
-                                      d.capacity, d.d_ff, d.d_model, act, s);
+                                      d.capacity, d.d_ff, d.d_model, act, s, x_rows);
     if (t0 && t1) (void)hipEventRecord(t1, s);
     return err;
 }
 
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
-                                  const void *w2, const void *b2, void *ye, hipStream_t s)
+                                  const void *w2, const void *b2, void *ye, hipStream_t s, void *y_tokens,
+                                  const float *gate)
 {
     const int N = d.n_groups * d.m_local;
+    // y_tokens: also (or, with ye == null, only) return the rows to token order, times the gate
+    const int32_t *y_rows = y_tokens ? ws.slot_token : nullptr;
     if (d.dtype == SMILE_DTYPE_BF16) {
-        GemmArgs g{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0};
+        GemmArgs g{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0, nullptr, y_rows, y_tokens, gate};
         return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
     }
     return launch_f32(static_cast<const float *>(ws.hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,
-                      d.d_model, d.d_ff, 0, s);
+                      d.d_model, d.d_ff, 0, s, nullptr, y_rows, static_cast<float *>(y_tokens), gate);
 }
 
 }  // namespace smile

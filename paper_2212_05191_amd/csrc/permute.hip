@@ -89,6 +89,42 @@ __global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
         if (dst[i] >= 0) xe[dst[i]] = v[i];
 }
 
+// Last routing step of the fully fused forward pass (no xe / ye buffers): one thread per token, one
+// workgroup per routing block.  Final slot and stage-1 position as in the routing finalize kernel;
+// kept tokens enter the slot -> token map that the expert GEMMs gather and scatter through; the
+// output rows of dropped tokens are zeroed here, a wave at a time (Eq. 3 gives them no expert output).
+__global__ __launch_bounds__(kRouteBlock) void finalize_map_kernel(
+    const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
+    const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
+    int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, int32_t *__restrict__ slot_token,
+    u32x4 *__restrict__ y, int T, int ppr, int n, int m, int C, LossArgs loss, float alpha, float beta)
+{
+    if (loss.out3 && blockIdx.x == gridDim.x - 1 && threadIdx.x < 64)
+        aux_loss_wave(loss.group_count, loss.local_count, loss.p_sum, loss.q_sum, T, n, m, alpha, beta, loss.out3);
+    const int b = blockIdx.x;
+    const int t = b * kRouteBlock + threadIdx.x;
+    const bool valid = t < T;
+    bool dropped = false;
+    if (valid) {
+        const int g = group_idx[t], e = g * m + local_idx[t];
+        const int rank = block_expert_off[(size_t)b * n * m + e] + rank_in_block[t];
+        const int sl = rank < C ? rank : -1;
+        slot[t] = sl;
+        pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
+        if (sl >= 0) slot_token[(size_t)e * C + sl] = t;
+        dropped = sl < 0;
+    }
+    unsigned long long mask = __ballot(dropped);
+    const int lane = threadIdx.x & 63, t0 = t - lane;
+    while (mask) {
+        const int src = __ffsll((long long)mask) - 1;
+        u32x4 *row = y + (size_t)(t0 + src) * ppr;
+        for (int p = lane; p < ppr; p += 64) row[p] = u32x4{0u, 0u, 0u, 0u};
+        mask &= mask - 1;
+    }
+}
+
 template <bool kBf16>
 __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 {
@@ -178,6 +214,19 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
                        static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist, ws.block_group_hist,
                        ws.rank_in_block, ws.pos_in_block, pos_in_group, slot, static_cast<u32x4 *>(xe), total, ppr,
                        d.n_groups, d.m_local, d.capacity, loss, d.T, d.alpha, d.beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, const int32_t *group_idx,
+                               const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
+                               const LossArgs &loss, hipStream_t s)
+{
+    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
+    hipLaunchKernelGGL(finalize_map_kernel, dim3(B), dim3(kRouteBlock), 0, s, group_idx, local_idx,
+                       ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group,
+                       slot, ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr, d.n_groups, d.m_local, d.capacity, loss,
+                       d.alpha, d.beta);
     return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ Layout workspace_layout(const smile_layer_desc &d)
     L.off_block_q_sum = off;       off = align_up(off + B * d.m_local * sizeof(float), 256);
     L.off_rank_in_block = off;     off = align_up(off + (size_t)d.T * sizeof(int32_t), 256);
     L.off_pos_in_block = off;      off = align_up(off + (size_t)d.T * sizeof(int32_t), 256);
+    L.off_slot_token = off;        off = align_up(off + N * (size_t)d.capacity * sizeof(int32_t), 256);
     L.off_hidden = off;            off = align_up(off + N * (size_t)d.capacity * d.d_ff * esz, 256);
     L.total = off;
     return L;
@@ -118,6 +119,7 @@ static smile_status make_ctx(const smile_layer_desc *desc, void *workspace, size
     c->ws.block_q_sum = reinterpret_cast<float *>(b + L.off_block_q_sum);
     c->ws.rank_in_block = reinterpret_cast<int32_t *>(b + L.off_rank_in_block);
     c->ws.pos_in_block = reinterpret_cast<int32_t *>(b + L.off_pos_in_block);
+    c->ws.slot_token = reinterpret_cast<int32_t *>(b + L.off_slot_token);
     c->ws.hidden = b + L.off_hidden;
     *out = c;
     return SMILE_OK;
@@ -254,23 +256,40 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         bad(io->logits_intra) || bad(io->group_idx) || bad(io->local_idx) || bad(io->pos_in_group) ||
         bad(io->slot) || bad(io->gate) || bad(io->p_top) || bad(io->q_top) || bad(io->group_count) ||
         bad(io->local_count) || bad(io->expert_count) || bad(io->kept_count) || bad(io->p_sum) ||
-        bad(io->q_sum) || bad(io->xe) || bad(io->ye) || bad(io->y) || bad(io->loss3))
+        bad(io->q_sum) || bad_opt(io->xe) || bad_opt(io->ye) || bad(io->y) || bad(io->loss3))
         return SMILE_INVALID_ARG;
+    if ((io->xe == nullptr) != (io->ye == nullptr)) return SMILE_INVALID_ARG;
     if ((io->prof_up_start == nullptr) != (io->prof_up_stop == nullptr)) return SMILE_INVALID_ARG;
-    // Same kernels as the step-by-step calls, with two launches saved: the last routing step (block
-    // offset + rank, capacity cut) and the loss both run inside the dispatch kernel.
+    // Same kernels as the step-by-step calls with fewer launches.  With expert buffers (xe, ye given):
+    // the last routing step and the loss run inside the dispatch kernel.  Without them (both NULL):
+    // nothing is materialised -- a per-token kernel finishes the routing, builds the slot -> token map
+    // and zeroes the rows of dropped tokens; the up GEMM gathers its rows from x through that map and
+    // the down GEMM returns gate-weighted rows straight to y.
     const smile_layer_desc &d = ctx->desc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool fused = io->xe == nullptr;
+    const LossArgs loss{io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3};
     hipError_t err = launch_gate_logits(d, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, s);
     if (err == hipSuccess)
         err = launch_route(d, ctx->ws, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
                            io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top, io->q_top,
                            io->group_count, io->local_count, io->expert_count, io->kept_count, io->p_sum, io->q_sum,
                            s, /*finalize=*/false);
+    if (fused) {
+        if (err == hipSuccess)
+            err = launch_finalize_map(d, ctx->ws, io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->y,
+                                      loss, s);
+        if (err == hipSuccess)
+            err = launch_expert_ffn_up(d, ctx->ws, nullptr, io->kept_count, io->w1, io->b1, s,
+                                       static_cast<hipEvent_t>(io->prof_up_start),
+                                       static_cast<hipEvent_t>(io->prof_up_stop), io->x);
+        if (err == hipSuccess)
+            err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, nullptr, s, io->y, io->gate);
+        return from_hip(err);
+    }
     if (err == hipSuccess)
         err = launch_dispatch_finalize(d, ctx->ws, io->x, io->group_idx, io->local_idx, io->pos_in_group, io->slot,
-                                       io->xe, LossArgs{io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3},
-                                       s);
+                                       io->xe, loss, s);
     if (err == hipSuccess)
         err = launch_expert_ffn_up(d, ctx->ws, io->xe, io->kept_count, io->w1, io->b1, s,
                                    static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop));

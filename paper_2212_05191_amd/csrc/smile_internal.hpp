@@ -20,13 +20,14 @@ struct Workspace {
     float *block_q_sum;           // [B][m]
     int32_t *rank_in_block;       // [T] rank among earlier tokens of the same block with the same expert
     int32_t *pos_in_block;        // [T] ... with the same group
+    int32_t *slot_token;          // [N][C] token sitting in each expert-buffer row (rows < kept only)
     // expert FFN: hidden activation between the two grouped GEMMs, ctx dtype
     void *hidden;                 // [N][C][F]
 };
 
 struct Layout {
     size_t off_block_expert_hist, off_block_group_hist, off_block_p_sum, off_block_q_sum, off_rank_in_block,
-        off_pos_in_block, off_hidden, total;
+        off_pos_in_block, off_slot_token, off_hidden, total;
     int32_t route_blocks;
 };
 
@@ -69,6 +70,12 @@ struct smile_ctx {
 
 namespace smile {
 
+struct LossArgs {
+    const int32_t *group_count, *local_count;
+    const float *p_sum, *q_sum;
+    float *out3;   // null: no loss
+};
+
 // Launchers: enqueue on `s`, return the launch status.  Shapes were validated by the caller.
 hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
                               float *logits_inter, float *logits_intra, hipStream_t s);
@@ -88,11 +95,6 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
 // dispatch fused with the last routing step: computes pos_in_group / slot from the workspace ranks
 // and block offsets, writes them, and moves the rows; loss != nullptr: one wave also evaluates Eq. 4
 // from the routing statistics (saves the separate loss launch)
-struct LossArgs {
-    const int32_t *group_count, *local_count;
-    const float *p_sum, *q_sum;
-    float *out3;   // null: no loss
-};
 hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
                                     int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s);
@@ -102,11 +104,21 @@ hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32
 
 // up: hidden = act(xe . w1^T + b1) into ws.hidden;  down: ye = hidden . w2^T + b2
 // t0/t1: optional events receiving the begin/end timestamps of the up kernel itself (both or neither)
+// x_tokens != nullptr: gather the input rows from the token matrix x[T,d] through ws.slot_token (xe unused)
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
-                                hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
+                                hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr, const void *x_tokens = nullptr);
+// y_tokens != nullptr: also write gate[t] * row to y_tokens[t] for the token t of each row (ye may be null)
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
-                                  const void *w2, const void *b2, void *ye, hipStream_t s);
+                                  const void *w2, const void *b2, void *ye, hipStream_t s,
+                                  void *y_tokens = nullptr, const float *gate = nullptr);
+
+// Last routing step for the fully fused forward pass: pos_in_group / slot as launch_route's finalize
+// kernel, plus the slot -> token map in ws.slot_token, zero output rows for dropped tokens in y, and
+// (loss.out3 != nullptr) the Eq. 4 loss.
+hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, const int32_t *group_idx,
+                               const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
+                               const LossArgs &loss, hipStream_t s);
 
 hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
                            const float *p_sum, const float *q_sum, float *out3, hipStream_t s);

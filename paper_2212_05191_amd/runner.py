@@ -58,6 +58,10 @@ class GpuLayer:
         self.buf = B.alloc_buffers(self.desc, device)
         self.io = B.make_io(self.x, self.w_inter, self.w_intra, self.w1, self.w2, self.buf, self.b1, self.b2,
                             self.bias_inter, self.bias_intra)
+        self.io_fused = B.make_io(self.x, self.w_inter, self.w_intra, self.w1, self.w2, self.buf, self.b1, self.b2,
+                                  self.bias_inter, self.bias_intra)
+        self.io_fused.xe = None
+        self.io_fused.ye = None
 
     # the six steps, one call each
     def gate_logits(self):
@@ -90,8 +94,12 @@ class GpuLayer:
         self.gate_logits(); self.route(); self.dispatch(); self.expert_ffn(); self.combine(); self.aux_loss()
 
     def forward(self):
-        """All six steps through the single chained entry point."""
+        """All six steps through the single chained entry point (expert buffers materialised)."""
         B.smile_layer_forward(self.ctx, self.io)
+
+    def forward_fused(self):
+        """The chained entry point without expert buffers: permutations fused into the expert GEMMs."""
+        B.smile_layer_forward(self.ctx, self.io_fused)
 
     def close(self):
         torch.cuda.synchronize()

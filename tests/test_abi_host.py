@@ -132,6 +132,9 @@ def test_entry_points_reject_bad_pointers_before_any_launch():
         io.y = None
         assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
         io.y = p
+        io.xe = None                # expert buffers come as a pair or not at all
+        assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
+        io.xe = p
         io.prof_up_stop = None      # timing events come as a pair or not at all
         assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
         assert lib.smile_expert_ffn_up_timed(h, p, p, p, None, p, None, None) == B.INVALID_ARG

@@ -43,6 +43,8 @@ def _run(cfg, forward="steps", **kw):
     layer.buf.ye.zero_()
     if forward == "steps":
         layer.forward_steps()
+    elif forward == "fused":
+        layer.forward_fused()
     else:
         layer.forward()
     return layer
@@ -90,6 +92,47 @@ def test_chained_entry_point_equals_step_by_step(torch_cuda):
     finally:
         a.close()
         b.close()
+
+
+FUSED_CASES = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[6], SMALL[10],
+               wl.small_config("fused_ragged", 4099, 128, 256, 4, 8, 100, "bf16", "gelu", skew=True, seed=26)]
+
+
+@pytest.mark.parametrize("cfg", FUSED_CASES, ids=lambda c: c.name)
+def test_fused_entry_point_equals_step_by_step(torch_cuda, cfg):
+    """smile_layer_forward without expert buffers (gather / scatter fused into the GEMMs) gives the same
+    bits as the six separate calls, and its y matches the oracle."""
+    a = _run(cfg, "steps")
+    b = _run(cfg, "fused")
+    try:
+        oa, ob = parity.fetch(a), parity.fetch(b)
+        for k in oa:
+            if k in ("xe", "ye"):
+                continue        # not produced by the fused path
+            np.testing.assert_array_equal(oa[k], ob[k], err_msg=k)
+        parity.check_full(cfg, a)
+    finally:
+        a.close()
+        b.close()
+
+
+def test_fused_entry_point_full_size(torch_cuda):
+    for name in ("cfg2", "cfg5"):
+        cfg = wl.get_config(name)
+        a = _run(cfg, "chained", workers=16)
+        y_ref = a.buf.y.clone()
+        loss_ref = a.buf.loss3.clone()
+        slot_ref = a.buf.slot.clone()
+        a.buf.y.fill_(-77)
+        a.buf.slot.fill_(-77)
+        a.buf.loss3.fill_(-77)
+        a.forward_fused()
+        torch_cuda.cuda.synchronize()
+        try:
+            assert bool((a.buf.y == y_ref).all()), name
+            assert bool((a.buf.slot == slot_ref).all()) and bool((a.buf.loss3 == loss_ref).all()), name
+        finally:
+            a.close()
 
 
 def test_repeated_calls_are_bit_identical(torch_cuda):
