@@ -117,7 +117,7 @@ def test_fused_entry_point_equals_step_by_step(torch_cuda, cfg):
 
 
 def test_fused_entry_point_full_size(torch_cuda):
-    for name in ("cfg2", "cfg5"):
+    for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
         cfg = wl.get_config(name)
         a = _run(cfg, "chained", workers=16)
         y_ref = a.buf.y.clone()
