@@ -65,6 +65,10 @@ SMALL = [
     # flat one-level routers (Section 2, Eq. 1-2 with k = 1): more than 128 logit columns -> two gate passes
     wl.small_config("flat_switch_200", 6000, 128, 128, 1, 200, 40, "bf16", "gelu", seed=24),
     wl.small_config("flat_switch_t_130", 3000, 64, 64, 130, 1, 30, "bf16", "relu", seed=25),
+    # the largest expert count the library accepts (N = 4096), capacity far above the load, fp32 with wider layers
+    wl.small_config("max_experts", 20000, 64, 64, 64, 64, 8, "bf16", "gelu", seed=27),
+    wl.small_config("capacity_above_T", 700, 128, 192, 2, 2, 1000, "bf16", "gelu", seed=28),
+    wl.small_config("f32_wider", 2100, 256, 512, 3, 3, 250, "f32", "gelu", seed=29),
 ]
 
 
