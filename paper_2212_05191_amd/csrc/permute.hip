@@ -1,9 +1,9 @@
 // Dispatch and combine: the token <-> expert-buffer row permutation (Section 3.2.1; on one GPU the
 // paper's inter- and intra-node hops are composed into a single row move) and the gate-weighted
 // return (Eq. 3).  Both are pure HBM streaming: a row is d*elem bytes (1.5-2 KiB for the bf16
-// configurations), moved as 16-byte pieces with consecutive lanes on consecutive pieces, so every
-// wave access is a run of full cache lines.  Each thread moves kPieces pieces spaced one grid-width
-// apart so that several loads are in flight per lane.
+// configurations), moved as 16-byte pieces; 8-32 consecutive lanes own a row, so every access is a
+// run of full cache lines, the routing indices are read once per row, and up to kPieces loads are
+// in flight per lane.
 #include "smile_internal.hpp"
 
 namespace smile {
@@ -17,76 +17,71 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
+// Row mapping shared by the kernels below: LPR consecutive lanes own one token row and walk its ppr
+// 16-byte pieces LPR at a time (so every access of those lanes is one contiguous run), kThreads / LPR
+// rows per workgroup.  The routing indices are read once per row, not once per piece.
+template <int LPR>
+struct RowLanes {
+    static constexpr int kRowsPerBlock = kThreads / LPR;
+    int t, sub;
+    __device__ __forceinline__ RowLanes() : t(blockIdx.x * kRowsPerBlock + threadIdx.x / LPR), sub(threadIdx.x % LPR) {}
+};
+
+// Copy (or gate-scale) one row, up to kPieces loads in flight per lane.  F maps a loaded piece to the stored one.
+template <int LPR, typename F>
+__device__ __forceinline__ void move_row(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int ppr, int sub, F f)
+{
+    for (int c0 = sub; c0 < ppr; c0 += LPR * kPieces) {
+        u32x4 v[kPieces];
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            if (c0 + i * LPR < ppr) v[i] = src[c0 + i * LPR];
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            if (c0 + i * LPR < ppr) dst[c0 + i * LPR] = f(v[i]);
+    }
+}
+
 // xe[(g*m+l)*C + slot] <- x[t] for kept tokens.  ppr = 16-byte pieces per row.
+template <int LPR>
 __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
-    const int32_t *__restrict__ slot, u32x4 *__restrict__ xe, long long total, int ppr, int m, int C)
+    const int32_t *__restrict__ slot, u32x4 *__restrict__ xe, int T, int ppr, int m, int C)
 {
-    const long long stride = (long long)gridDim.x * kThreads;
-    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
-    u32x4 v[kPieces];
-    long long dst[kPieces];
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i) {
-        const long long p = id + i * stride;
-        dst[i] = -1;
-        if (p < total) {
-            const int t = (int)(p / ppr);
-            const int c = (int)(p - (long long)t * ppr);
-            const int sl = slot[t];
-            if (sl >= 0) {
-                dst[i] = ((long long)(group_idx[t] * m + local_idx[t]) * C + sl) * ppr + c;
-                v[i] = x[p];
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i)
-        if (dst[i] >= 0) xe[dst[i]] = v[i];
+    const RowLanes<LPR> rl;
+    if (rl.t >= T) return;
+    const int sl = slot[rl.t];
+    if (sl < 0) return;
+    const size_t row = (size_t)(group_idx[rl.t] * m + local_idx[rl.t]) * C + sl;
+    move_row<LPR>(x + (size_t)rl.t * ppr, xe + row * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
 }
 
 // Dispatch fused with the last routing step (the chained forward pass): every thread derives the
 // token's final slot from the workspace (block offset of its expert + rank inside the block,
 // dropped at or beyond C); the thread moving piece 0 of a token also writes slot / pos_in_group.
+template <int LPR>
 __global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
     const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
     const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
     int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, u32x4 *__restrict__ xe,
-    long long total, int ppr, int n, int m, int C, LossArgs loss, int T, float alpha, float beta)
+    int T, int ppr, int n, int m, int C, LossArgs loss, float alpha, float beta)
 {
     // Eq. 4 from the (complete) routing statistics, by the first wave of the last workgroup
     if (loss.out3 && blockIdx.x == gridDim.x - 1 && threadIdx.x < 64)
         aux_loss_wave(loss.group_count, loss.local_count, loss.p_sum, loss.q_sum, T, n, m, alpha, beta, loss.out3);
-    const long long stride = (long long)gridDim.x * kThreads;
-    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
-    const int N = n * m;
-    u32x4 v[kPieces];
-    long long dst[kPieces];
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i) {
-        const long long p = id + i * stride;
-        dst[i] = -1;
-        if (p < total) {
-            const int t = (int)(p / ppr);
-            const int c = (int)(p - (long long)t * ppr);
-            const int b = t / kRouteBlock;
-            const int g = group_idx[t], e = g * m + local_idx[t];
-            const int rank = block_expert_off[(size_t)b * N + e] + rank_in_block[t];
-            const int sl = rank < C ? rank : -1;
-            if (c == 0) {
-                slot[t] = sl;
-                pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
-            }
-            if (sl >= 0) {
-                dst[i] = ((long long)e * C + sl) * ppr + c;
-                v[i] = x[p];
-            }
-        }
+    const RowLanes<LPR> rl;
+    if (rl.t >= T) return;
+    const int t = rl.t, b = t / kRouteBlock;
+    const int g = group_idx[t], e = g * m + local_idx[t];
+    const int rank = block_expert_off[(size_t)b * n * m + e] + rank_in_block[t];
+    const int sl = rank < C ? rank : -1;
+    if (rl.sub == 0) {
+        slot[t] = sl;
+        pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
     }
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i)
-        if (dst[i] >= 0) xe[dst[i]] = v[i];
+    if (sl < 0) return;
+    move_row<LPR>(x + (size_t)t * ppr, xe + ((size_t)e * C + sl) * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
 }
 
 // Last routing step of the fully fused forward pass (no xe / ye buffers): one thread per token, one
@@ -148,58 +143,51 @@ __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 }
 
 // y[t] <- gate[t] * ye[(g*m+l)*C + slot] for kept tokens, 0 for dropped ones.
-template <bool kBf16>
+template <bool kBf16, int LPR>
 __global__ __launch_bounds__(kThreads) void combine_kernel(
     const u32x4 *__restrict__ ye, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ slot, const float *__restrict__ gate, u32x4 *__restrict__ y,
-    long long total, int ppr, int m, int C)
+    int T, int ppr, int m, int C)
 {
-    const long long stride = (long long)gridDim.x * kThreads;
-    long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
-    u32x4 v[kPieces];
-    float gt[kPieces];
-    bool kept[kPieces];
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i) {
-        const long long p = id + i * stride;
-        v[i] = u32x4{0u, 0u, 0u, 0u};
-        gt[i] = 0.f;
-        kept[i] = false;
-        if (p < total) {
-            const int t = (int)(p / ppr);
-            const int c = (int)(p - (long long)t * ppr);
-            const int sl = slot[t];
-            if (sl >= 0) {
-                v[i] = ye[((long long)(group_idx[t] * m + local_idx[t]) * C + sl) * ppr + c];
-                gt[i] = gate[t];
-                kept[i] = true;
-            }
-        }
+    const RowLanes<LPR> rl;
+    if (rl.t >= T) return;
+    const int sl = slot[rl.t];
+    u32x4 *dst = y + (size_t)rl.t * ppr;
+    if (sl < 0) {
+        for (int c = rl.sub; c < ppr; c += LPR) dst[c] = u32x4{0u, 0u, 0u, 0u};
+        return;
     }
-#pragma unroll
-    for (int i = 0; i < kPieces; ++i) {
-        const long long p = id + i * stride;
-        if (p < total) y[p] = kept[i] ? scale_piece<kBf16>(v[i], gt[i]) : u32x4{0u, 0u, 0u, 0u};
-    }
+    const float gt = gate[rl.t];
+    const size_t row = (size_t)(group_idx[rl.t] * m + local_idx[rl.t]) * C + sl;
+    move_row<LPR>(ye + row * ppr, dst, ppr, rl.sub, [gt](u32x4 v) { return scale_piece<kBf16>(v, gt); });
 }
 
-int grid_for(long long total)
+// lanes per row: the largest power of two <= min(ppr, 64), at least 8 (ppr >= 8 for every accepted shape... d >= 64 bf16, d >= 32 fp32)
+int lanes_per_row(int ppr)
 {
-    const long long per_block = (long long)kThreads * kPieces;
-    return (int)((total + per_block - 1) / per_block);
+    int l = 8;
+    while (l * 2 <= ppr && l < 32) l *= 2;
+    return l;
 }
 
 }  // namespace
 
+#define SMILE_LPR_SWITCH(lpr, CALL)          \
+    switch (lpr) {                           \
+    case 8: { constexpr int L = 8; CALL; } break;   \
+    case 16: { constexpr int L = 16; CALL; } break; \
+    default: { constexpr int L = 32; CALL; } break; \
+    }
+
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s)
 {
-    const int esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
-    const int ppr = d.d_model * esz / 16;
-    const long long total = (long long)d.T * ppr;
-    hipLaunchKernelGGL(dispatch_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
-                       static_cast<const u32x4 *>(x), group_idx, local_idx, slot, static_cast<u32x4 *>(xe), total,
-                       ppr, d.m_local, d.capacity);
+    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int lpr = lanes_per_row(ppr);
+    const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
+    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
+                                             group_idx, local_idx, slot, static_cast<u32x4 *>(xe), d.T, ppr, d.m_local,
+                                             d.capacity));
     return hipGetLastError();
 }
 
@@ -207,13 +195,14 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
                                     int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s)
 {
-    const int esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
-    const int ppr = d.d_model * esz / 16;
-    const long long total = (long long)d.T * ppr;
-    hipLaunchKernelGGL(dispatch_finalize_kernel, dim3(grid_for(total)), dim3(kThreads), 0, s,
-                       static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist, ws.block_group_hist,
-                       ws.rank_in_block, ws.pos_in_block, pos_in_group, slot, static_cast<u32x4 *>(xe), total, ppr,
-                       d.n_groups, d.m_local, d.capacity, loss, d.T, d.alpha, d.beta);
+    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int lpr = lanes_per_row(ppr);
+    const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
+    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_finalize_kernel<L>, grid, block, 0, s,
+                                             static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist,
+                                             ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group, slot,
+                                             static_cast<u32x4 *>(xe), d.T, ppr, d.n_groups, d.m_local, d.capacity, loss,
+                                             d.alpha, d.beta));
     return hipGetLastError();
 }
 
@@ -235,14 +224,17 @@ hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32
 {
     const bool bf = d.dtype == SMILE_DTYPE_BF16;
     const int ppr = d.d_model * (bf ? 2 : 4) / 16;
-    const long long total = (long long)d.T * ppr;
-    const dim3 grid(grid_for(total)), block(kThreads);
-    if (bf)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, static_cast<const u32x4 *>(ye), group_idx,
-                           local_idx, slot, gate, static_cast<u32x4 *>(y), total, ppr, d.m_local, d.capacity);
-    else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, static_cast<const u32x4 *>(ye), group_idx,
-                           local_idx, slot, gate, static_cast<u32x4 *>(y), total, ppr, d.m_local, d.capacity);
+    const int lpr = lanes_per_row(ppr);
+    const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
+    if (bf) {
+        SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<true, L>), grid, block, 0, s,
+                                                 static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
+                                                 static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity));
+    } else {
+        SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<false, L>), grid, block, 0, s,
+                                                 static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
+                                                 static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity));
+    }
     return hipGetLastError();
 }
 
