@@ -41,21 +41,51 @@ __device__ __forceinline__ unsigned long long match_any(int key, int bits, bool 
     return mask;
 }
 
+// exp(v) for v <= 0 by the hardware exp2 (v_exp_f32 is accurate to about 1 ulp; the scaling by
+// log2(e) adds a relative error of about |v| * 6e-8, far inside the 1e-5 tolerance of the gates).
+// The kernel is instruction-bound (one wave per SIMD at T = 65536), which is why this matters.
+__device__ __forceinline__ float exp_neg(float v)
+{
+    return __builtin_amdgcn_exp2f(v * 1.4426950408889634f);
+}
+
+constexpr int kLoadChunk = 8;   // logits fetched per lane before any of them is used (loads in flight)
+
+// kLoadChunk biased logits starting at column i0 (one fp32 add each; columns >= len give `fill`).
+// All loads are issued before the first use, so a lane waits for memory once per chunk, not per logit.
+__device__ __forceinline__ void load_biased(const float *__restrict__ row, const float *__restrict__ bias, int i0,
+                                            int len, float fill, float (&a)[kLoadChunk])
+{
+    float v[kLoadChunk], bv[kLoadChunk];
+#pragma unroll
+    for (int k = 0; k < kLoadChunk; ++k) {
+        const int i = min(i0 + k, len - 1);
+        v[k] = row[i];
+        bv[k] = bias ? bias[i] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < kLoadChunk; ++k) a[k] = i0 + k < len ? (bias ? __fadd_rn(v[k], bv[k]) : v[k]) : fill;
+}
+
 // Top-1 over `len` biased logits: lowest index of the maximum, and 1/sum(exp(a - max)) which is
 // the softmax probability of that maximum.  `row` and `bias` (may be null) are read twice.
 __device__ __forceinline__ void top1_softmax(const float *__restrict__ row, const float *__restrict__ bias,
                                              int len, int &arg, float &mx, float &inv_z)
 {
     arg = 0;
-    mx = bias ? __fadd_rn(row[0], bias[0]) : row[0];
-    for (int i = 1; i < len; ++i) {
-        const float a = bias ? __fadd_rn(row[i], bias[i]) : row[i];
-        if (a > mx) { mx = a; arg = i; }
+    mx = -INFINITY;
+    float a[kLoadChunk];
+    for (int i0 = 0; i0 < len; i0 += kLoadChunk) {
+        load_biased(row, bias, i0, len, -INFINITY, a);
+#pragma unroll
+        for (int k = 0; k < kLoadChunk; ++k)
+            if (a[k] > mx) { mx = a[k]; arg = i0 + k; }   // strict: the lowest index of the maximum wins
     }
     float z = 0.f;
-    for (int i = 0; i < len; ++i) {
-        const float a = bias ? __fadd_rn(row[i], bias[i]) : row[i];
-        z += expf(a - mx);
+    for (int i0 = 0; i0 < len; i0 += kLoadChunk) {
+        load_biased(row, bias, i0, len, -INFINITY, a);
+#pragma unroll
+        for (int k = 0; k < kLoadChunk; ++k) z += exp_neg(a[k] - mx);   // exp2(-inf) = 0 for the padding
     }
     inv_z = 1.0f / z;
 }
@@ -70,13 +100,12 @@ __device__ __forceinline__ void block_column_sums(const float *__restrict__ row,
     const int tid = threadIdx.x;
     for (int c0 = 0; c0 < len; c0 += kColChunk) {
         const int w = min(kColChunk, len - c0);
-        for (int i = 0; i < w; ++i) {
-            float p = 0.f;
-            if (valid) {
-                const float a = bias ? __fadd_rn(row[c0 + i], bias[c0 + i]) : row[c0 + i];
-                p = expf(a - mx) * inv_z;
-            }
-            tile[tid][i] = p;
+        for (int i0 = 0; i0 < w; i0 += kLoadChunk) {
+            float a[kLoadChunk];
+            if (valid) load_biased(row, bias, c0 + i0, len, -INFINITY, a);
+#pragma unroll
+            for (int k = 0; k < kLoadChunk; ++k)
+                if (i0 + k < w) tile[tid][i0 + k] = valid ? exp_neg(a[k] - mx) * inv_z : 0.f;
         }
         __syncthreads();
         const int col = tid & (kColChunk - 1), seg = tid / kColChunk;   // 8 segments of 32 tokens
