@@ -10,6 +10,8 @@ from .oracle import (  # noqa: F401
     route,
     slots_two_stage,
     dispatch,
+    dispatch_stage1,
+    dispatch_stage2,
     expert_ffn,
     combine,
     aux_loss,

@@ -96,7 +96,8 @@ class RouteResult:
     q_sum: np.ndarray
 
 
-def route(logits_inter, logits_intra, capacity_rows: int, bias_inter=None, bias_intra=None) -> RouteResult:
+def route(logits_inter, logits_intra, capacity_rows: int, bias_inter=None, bias_intra=None,
+          group_capacity: int = 0) -> RouteResult:
     li, lq = _f32(logits_inter), _f32(logits_intra)
     T, n = li.shape
     m = lq.shape[1]
@@ -110,7 +111,7 @@ def route(logits_inter, logits_intra, capacity_rows: int, bias_inter=None, bias_
         np.empty(n, np.int32), np.empty(m, np.int32), np.empty(N, np.int32), np.empty(N, np.int32),
         np.empty(n, np.float64), np.empty(m, np.float64))
     _load().smile_oracle_route(_p(li), _p(lq), _p(bi), _p(bq), C.c_int32(T), C.c_int32(n), C.c_int32(m),
-                               C.c_int32(int(capacity_rows)),
+                               C.c_int32(int(capacity_rows)), C.c_int32(int(group_capacity)),
                                _p(r.group_idx), _p(r.local_idx), _p(r.pos_in_group), _p(r.slot),
                                _p(r.gate), _p(r.p_top), _p(r.q_top),
                                _p(r.group_count), _p(r.local_count), _p(r.expert_count), _p(r.kept_count),
@@ -118,14 +119,36 @@ def route(logits_inter, logits_intra, capacity_rows: int, bias_inter=None, bias_
     return r
 
 
-def slots_two_stage(group_idx, local_idx, n: int, m: int, capacity_rows: int):
+def slots_two_stage(group_idx, local_idx, n: int, m: int, capacity_rows: int, group_capacity: int = 0):
     g, l = _i32(group_idx), _i32(local_idx)
     T = g.shape[0]
     pos = np.full(T, -7, np.int32)
     slot = np.full(T, -7, np.int32)
     _load().smile_oracle_slots_two_stage(_p(g), _p(l), C.c_int32(T), C.c_int32(n), C.c_int32(m),
-                                         C.c_int32(int(capacity_rows)), _p(pos), _p(slot))
+                                         C.c_int32(int(capacity_rows)), C.c_int32(int(group_capacity)), _p(pos),
+                                         _p(slot))
     return pos, slot
+
+
+def dispatch_stage1(x, group_idx, pos_in_group, n: int, group_rows: int, fill: float = 0.0):
+    x = _f32(x)
+    T, d = x.shape
+    xg = np.full((n, int(group_rows), d), fill, np.float32)
+    _load().smile_oracle_dispatch_stage1(_p(x), _p(_i32(group_idx)), _p(_i32(pos_in_group)), C.c_int32(T),
+                                         C.c_int32(d), C.c_int32(int(group_rows)), _p(xg))
+    return xg
+
+
+def dispatch_stage2(xg, group_idx, local_idx, pos_in_group, slot, m: int, capacity_rows: int, fill: float = 0.0):
+    xg = _f32(xg)
+    n, Cg, d = xg.shape
+    g = _i32(group_idx)
+    T = g.shape[0]
+    xe = np.full((n * m, int(capacity_rows), d), fill, np.float32)
+    _load().smile_oracle_dispatch_stage2(_p(xg), _p(g), _p(_i32(local_idx)), _p(_i32(pos_in_group)), _p(_i32(slot)),
+                                         C.c_int32(T), C.c_int32(d), C.c_int32(m), C.c_int32(int(capacity_rows)),
+                                         C.c_int32(Cg), _p(xe))
+    return xe
 
 
 def dispatch(x, group_idx, local_idx, slot, n: int, m: int, capacity_rows: int, fill: float = 0.0):
@@ -177,11 +200,11 @@ def aux_loss(group_count, local_count, p_sum, q_sum, T: int, alpha: float, beta:
 
 def layer_forward(x, w_inter, w_intra, w1, w2, capacity_rows: int, act: str, dtype: str,
                   alpha: float = 0.005, beta: float = 0.005, bias_inter=None, bias_intra=None,
-                  logits=None):
+                  logits=None, group_capacity: int = 0):
     """Chain the steps of one layer forward.  `logits` (inter, intra) overrides step 1."""
     n, m = np.shape(w_inter)[0], np.shape(w_intra)[0]
     li, lq = gate_logits(x, w_inter, w_intra) if logits is None else logits
-    r = route(li, lq, capacity_rows, bias_inter, bias_intra)
+    r = route(li, lq, capacity_rows, bias_inter, bias_intra, group_capacity)
     xe = dispatch(x, r.group_idx, r.local_idx, r.slot, n, m, capacity_rows)
     ye = expert_ffn(xe, r.kept_count, w1, w2, act, dtype)
     y = combine(ye, r.group_idx, r.local_idx, r.slot, r.gate, m, dtype)

@@ -133,17 +133,25 @@ static int32_t softmax_top1(const float *a, int32_t len, double *prob)
  * dropped (slot = -1) once C slots are taken.  pos_in_group is the token's
  * rank among the tokens of its group (the first-stage position).
  *
+ * Optional group-level capacity Cg (Cg <= 0: none): the first hop of
+ * Section 3.2.3 (the inter-node All2All) also has a buffer of fixed size per
+ * group.  A token whose pos_in_group is >= Cg is dropped at that hop: it never
+ * reaches the second hop, so it takes no expert slot and does not push later
+ * tokens of its expert out.  The statistics of Section 3.2.2 (counts, sums)
+ * are those of the router and ignore both kinds of drops.
+ *
  * bias_inter[n] and bias_intra[n,m] may be NULL.
  */
 void smile_oracle_route(const float *logits_inter, const float *logits_intra,
                         const float *bias_inter, const float *bias_intra,
-                        int32_t T, int32_t n, int32_t m, int32_t C,
+                        int32_t T, int32_t n, int32_t m, int32_t C, int32_t Cg,
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot,
                         double *gate, double *p_top, double *q_top,
                         int32_t *group_count, int32_t *local_count, int32_t *expert_count,
                         int32_t *kept_count, double *p_sum, double *q_sum)
 {
     const int32_t N = n * m;
+    int32_t *arrived = (int32_t *)calloc((size_t)N, sizeof(int32_t));   /* tokens that reached expert e */
     float *a = (float *)malloc(sizeof(float) * (size_t)(n > m ? n : m));
     double *pr = (double *)malloc(sizeof(double) * (size_t)(n > m ? n : m));
     for (int32_t i = 0; i < n; ++i) { group_count[i] = 0; p_sum[i] = 0.0; }
@@ -178,16 +186,20 @@ void smile_oracle_route(const float *logits_inter, const float *logits_intra,
 
         /* slots in token order */
         int32_t e = g * m + l;
-        pos_in_group[t] = group_count[g];
+        int32_t pos1 = group_count[g];
+        pos_in_group[t] = pos1;
         group_count[g] += 1;
         local_count[l] += 1;
-        int32_t s = expert_count[e];
         expert_count[e] += 1;
+        if (Cg > 0 && pos1 >= Cg) { slot[t] = -1; continue; }   /* dropped at the first hop */
+        int32_t s = arrived[e];
+        arrived[e] += 1;
         if (s < C) { slot[t] = s; kept_count[e] += 1; }
         else slot[t] = -1;
     }
     free(a);
     free(pr);
+    free(arrived);
 }
 
 /* The same slot assignment done literally in two stages, as the two
@@ -196,7 +208,7 @@ void smile_oracle_route(const float *logits_inter, const float *logits_intra,
  * in that order and buckets by local expert, dropping what exceeds C.
  * Used to check that the composed single move equals the two-stage one. */
 void smile_oracle_slots_two_stage(const int32_t *group_idx, const int32_t *local_idx,
-                                  int32_t T, int32_t n, int32_t m, int32_t C,
+                                  int32_t T, int32_t n, int32_t m, int32_t C, int32_t Cg,
                                   int32_t *pos_in_group, int32_t *slot)
 {
     int32_t *bucket = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
@@ -205,6 +217,10 @@ void smile_oracle_slots_two_stage(const int32_t *group_idx, const int32_t *local
         int32_t len = 0;
         for (int32_t t = 0; t < T; ++t)          /* stage 1 */
             if (group_idx[t] == i) { pos_in_group[t] = len; bucket[len++] = t; }
+        if (Cg > 0 && len > Cg) {                 /* the group's buffer holds Cg tokens: the rest is dropped */
+            for (int32_t r = Cg; r < len; ++r) slot[bucket[r]] = -1;
+            len = Cg;
+        }
         for (int32_t j = 0; j < m; ++j) fill[j] = 0;
         for (int32_t r = 0; r < len; ++r) {       /* stage 2 */
             int32_t t = bucket[r], j = local_idx[t];
@@ -226,6 +242,33 @@ void smile_oracle_dispatch(const float *x, const int32_t *group_idx, const int32
         if (slot[t] < 0) continue;
         size_t row = ((size_t)(group_idx[t] * m + local_idx[t]) * C + (size_t)slot[t]);
         memcpy(xe + row * d, x + (size_t)t * d, sizeof(float) * (size_t)d);
+    }
+}
+
+/* The same move done in two hops (Section 3.2.3).  Hop 1: token t goes to row
+ * pos_in_group[t] of the buffer of its group, xg[n,Cg,d], unless that row does
+ * not exist (pos_in_group[t] >= Cg).  Hop 2: a kept token goes from there to
+ * row slot[t] of its expert's buffer.  Rows that receive nothing keep the
+ * caller's values. */
+void smile_oracle_dispatch_stage1(const float *x, const int32_t *group_idx, const int32_t *pos_in_group,
+                                  int32_t T, int32_t d, int32_t Cg, float *xg)
+{
+    for (int32_t t = 0; t < T; ++t) {
+        if (pos_in_group[t] >= Cg) continue;
+        memcpy(xg + ((size_t)group_idx[t] * Cg + (size_t)pos_in_group[t]) * d, x + (size_t)t * d,
+               sizeof(float) * (size_t)d);
+    }
+}
+
+void smile_oracle_dispatch_stage2(const float *xg, const int32_t *group_idx, const int32_t *local_idx,
+                                  const int32_t *pos_in_group, const int32_t *slot,
+                                  int32_t T, int32_t d, int32_t m, int32_t C, int32_t Cg, float *xe)
+{
+    for (int32_t t = 0; t < T; ++t) {
+        if (slot[t] < 0) continue;
+        size_t row = ((size_t)(group_idx[t] * m + local_idx[t]) * C + (size_t)slot[t]);
+        memcpy(xe + row * d, xg + ((size_t)group_idx[t] * Cg + (size_t)pos_in_group[t]) * d,
+               sizeof(float) * (size_t)d);
     }
 }
 

@@ -190,6 +190,104 @@ def test_load_never_exceeds_capacity_and_slots_are_dense(rng, C):
         assert (r.slot < 0).any()
 
 
+# ------------------------------------------------------------------ group-level capacity (first hop of Section 3.2.3)
+
+@pytest.mark.parametrize("seed", range(10))
+def test_group_capacity_bruteforce_tiny(seed):
+    rng = np.random.default_rng(500 + seed)
+    T = int(rng.integers(4, 25))
+    n = int(rng.integers(1, 4))
+    m = int(rng.integers(1, 4))
+    C = int(rng.integers(1, 5))
+    Cg = int(rng.integers(1, 8))
+    li, lq = _rand_logits(rng, T, n, m)
+    r0 = oracle.route(li, lq, C)                 # the routing decisions do not depend on either capacity
+    r = oracle.route(li, lq, C, group_capacity=Cg)
+    for k in ("group_idx", "local_idx", "pos_in_group", "gate", "group_count", "local_count", "expert_count",
+              "p_sum", "q_sum"):
+        np.testing.assert_array_equal(getattr(r, k), getattr(r0, k))
+    e = r.group_idx * m + r.local_idx
+    kept = np.zeros(n * m, int)
+    for t in range(T):
+        # literal definitions: the token passes hop 1 if fewer than Cg earlier tokens chose its group; its slot
+        # is the number of earlier tokens of its expert that also passed hop 1
+        passed = [sum(1 for v in range(u) if r.group_idx[v] == r.group_idx[u]) < Cg for u in range(t + 1)]
+        rank = sum(1 for u in range(t) if e[u] == e[t] and passed[u])
+        want = rank if (passed[t] and rank < C) else -1
+        assert r.slot[t] == want
+        kept[e[t]] += want >= 0
+    np.testing.assert_array_equal(r.kept_count, kept)
+
+
+def test_group_capacity_invariants(rng):
+    T, n, m, C = 600, 3, 4, 40
+    li, lq = _rand_logits(rng, T, n, m, scale=2.0)
+    bi = np.array([1.0, 0.0, -1.0], np.float32)            # unequal groups: the largest overflows first
+    free = oracle.route(li, lq, C, bi)
+    # a cap no group reaches changes nothing; zero or a negative value means "no cap"
+    for Cg in (0, -3, int(free.group_count.max()), T):
+        r = oracle.route(li, lq, C, bi, group_capacity=Cg)
+        np.testing.assert_array_equal(r.slot, free.slot)
+        np.testing.assert_array_equal(r.kept_count, free.kept_count)
+    Cg = int(free.group_count.max()) // 2
+    r = oracle.route(li, lq, C, bi, group_capacity=Cg)
+    assert (r.slot[r.pos_in_group >= Cg] == -1).all() and (r.pos_in_group >= Cg).any()
+    # per group, no more than Cg tokens go on, and no expert holds more than C
+    through = np.bincount(r.group_idx[r.pos_in_group < Cg], minlength=n)
+    np.testing.assert_array_equal(through, np.minimum(free.group_count, Cg))
+    assert r.kept_count.max() <= C and (r.slot >= 0).sum() == r.kept_count.sum()
+    # a token dropped at hop 1 frees a slot: nobody who was kept without the cap and passes hop 1 is dropped now
+    assert np.all(r.slot[(free.slot >= 0) & (r.pos_in_group < Cg)] >= 0)
+    # kept slots stay dense and in token order
+    e = r.group_idx * m + r.local_idx
+    for ex in range(n * m):
+        np.testing.assert_array_equal(r.slot[(e == ex) & (r.slot >= 0)], np.arange(r.kept_count[ex]))
+    # the literal two-hop bucketing gives the same slots
+    pos, slot = oracle.slots_two_stage(r.group_idx, r.local_idx, n, m, C, Cg)
+    np.testing.assert_array_equal(pos, r.pos_in_group)
+    np.testing.assert_array_equal(slot, r.slot)
+    # Cg = m*C with one local expert per group is the same cap applied twice
+    r1 = oracle.route(li, lq[:, :1], C, bi, group_capacity=C)
+    r2 = oracle.route(li, lq[:, :1], C, bi)
+    np.testing.assert_array_equal(r1.slot, r2.slot)
+
+
+def test_two_hop_dispatch_composes_to_the_one_hop_move(rng):
+    T, n, m, C, d = 300, 3, 2, 30, 8
+    li, lq = _rand_logits(rng, T, n, m, scale=2.0)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    for Cg in (45, 500):
+        r = oracle.route(li, lq, C, group_capacity=Cg)
+        rows = min(Cg, T)
+        xg = oracle.dispatch_stage1(x, r.group_idx, r.pos_in_group, n, rows, fill=-7.0)
+        # hop 1 by fancy indexing: row (g, pos1) of the group buffer holds the token, other rows are untouched
+        want = np.full((n, rows, d), -7.0, np.float32)
+        ok = r.pos_in_group < rows
+        want[r.group_idx[ok], r.pos_in_group[ok]] = x[ok]
+        np.testing.assert_array_equal(xg, want)
+        xe2 = oracle.dispatch_stage2(xg, r.group_idx, r.local_idx, r.pos_in_group, r.slot, m, C)
+        xe1 = oracle.dispatch(x, r.group_idx, r.local_idx, r.slot, n, m, C)
+        np.testing.assert_array_equal(xe2, xe1)
+        assert (r.slot < 0).any()
+
+
+def test_group_capacity_layer_output_rows(rng):
+    # a token dropped at hop 1 gets a zero output row, like one dropped at the expert
+    T, n, m, C, d, F = 64, 2, 2, 64, 8, 16
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    wi = rng.standard_normal((n, d)).astype(np.float32)
+    wq = rng.standard_normal((m, d)).astype(np.float32)
+    w1 = rng.standard_normal((n * m, F, d)).astype(np.float32)
+    w2 = rng.standard_normal((n * m, d, F)).astype(np.float32)
+    full = oracle.layer_forward(x, wi, wq, w1, w2, C, "relu", "f32")
+    cut = oracle.layer_forward(x, wi, wq, w1, w2, C, "relu", "f32", group_capacity=10)
+    late = cut["route"].pos_in_group >= 10
+    assert late.any() and (~late).any()
+    assert np.all(cut["y"][late] == 0)
+    np.testing.assert_array_equal(cut["y"][~late], full["y"][~late])
+    np.testing.assert_array_equal(cut["loss"], full["loss"])     # Eq. 4 sees the router, not the drops
+
+
 # ------------------------------------------------------------------ n = 1 is Switch top-1 routing
 
 def _switch_top1_layer(x, w_r, w1, w2, C, act):
