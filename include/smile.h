@@ -28,7 +28,8 @@
  *     probabilities, gates and the loss are always fp32.
  *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for bf16:
  *     d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096;
- *     N*C*max(d,F) < 2^40 elements; N*C and T below 2^31.  n = 1 (or m = 1)
+ *     N*C*max(d,F) < 2^40 elements; N*C and T below 2^31 (T <= 2^30 with a
+ *     group capacity).  n = 1 (or m = 1)
  *     gives the flat one-level top-1 router of Section 2 (Eq. 1-2, k = 1).
  *   - Floating-point inputs must be finite; NaN/Inf give unspecified results.
  */
@@ -66,6 +67,7 @@ typedef struct smile_layer_desc {
     int32_t act;        /* SMILE_ACT_* */
     float alpha;        /* Eq. 4 coefficients */
     float beta;
+    int32_t group_capacity;   /* Cg: rows of each group's first-hop buffer (Section 3.2.3); 0 = no limit */
 } smile_layer_desc;
 
 typedef struct smile_ctx smile_ctx;   /* opaque: a validated desc + device workspace */
@@ -120,6 +122,10 @@ smile_status smile_gate_logits(smile_ctx *ctx, const void *x, const void *w_inte
  *   pos_in_group[t] = number of earlier tokens with the same group       (stage-1 position)
  *   rank = number of earlier tokens with the same (group, local)          (stage-2 position)
  *   slot[t] = rank if rank < C, else -1 (token dropped)
+ *   With desc.group_capacity = Cg > 0 the first hop of Section 3.2.3 has a buffer of Cg rows per
+ *   group as well: a token with pos_in_group[t] >= Cg is dropped there (slot -1) and is not counted
+ *   in `rank` of later tokens; kept_count[e] is then min(tokens of e that passed the first hop, C).
+ *   The counts and sums below ignore both kinds of drops.
  *   group_count[n], local_count[m] (summed over all groups), expert_count[N]: top-1 counts of all T
  *   tokens, before drops;  kept_count[e] = min(expert_count[e], C);
  *   p_sum[i] = sum_t p[t,i];  q_sum[j] = sum_t q[t,j]    (fp32)
@@ -138,6 +144,20 @@ smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, cons
  * kept_count[e] are not written. */
 smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_idx, const int32_t *local_idx,
                             const int32_t *slot, void *xe, void *stream);
+
+/* The same move as the two hops of Section 3.2.3, with the first-hop buffer materialised (what the
+ * inter-node All2All delivers): xg[n, group_rows, d] in the ctx dtype.
+ *   hop 1: xg[group_idx[t], pos_in_group[t], :] = x[t, :]        for pos_in_group[t] < group_rows
+ *   hop 2: xe[e, slot[t], :] = xg[group_idx[t], pos_in_group[t], :]   for slot[t] >= 0
+ * group_rows >= 1; with a group capacity it is normally desc.group_capacity, without one any value
+ * not below the largest group_count.  hop 2 requires pos_in_group[t] < group_rows for every kept
+ * token (true for the outputs of smile_route_bilevel under the rule above) and does not check it on
+ * the device beyond skipping such tokens.  Rows that receive nothing are not written. */
+smile_status smile_dispatch_hop1(smile_ctx *ctx, const void *x, const int32_t *group_idx,
+                                 const int32_t *pos_in_group, int32_t group_rows, void *xg, void *stream);
+smile_status smile_dispatch_hop2(smile_ctx *ctx, const void *xg, const int32_t *group_idx,
+                                 const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
+                                 int32_t group_rows, void *xe, void *stream);
 
 /* Step 3 -- expert FFN E_e of Eq. 3 (Section 4.1: hidden -> intermediate ->
  * hidden with the activation of the ctx) on rows r < kept_count[e]:

@@ -29,7 +29,7 @@ class SmileError(RuntimeError):
 class LayerDesc(C.Structure):
     _fields_ = [("T", C.c_int32), ("d_model", C.c_int32), ("d_ff", C.c_int32), ("n_groups", C.c_int32),
                 ("m_local", C.c_int32), ("capacity", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
-                ("alpha", C.c_float), ("beta", C.c_float)]
+                ("alpha", C.c_float), ("beta", C.c_float), ("group_capacity", C.c_int32)]
 
 
 class LayerIO(C.Structure):
@@ -43,7 +43,7 @@ class LayerIO(C.Structure):
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
-    "smile_dispatch", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
+    "smile_dispatch", "smile_dispatch_hop1", "smile_dispatch_hop2", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
 )
 
 
@@ -70,6 +70,8 @@ def load() -> C.CDLL:
     lib.smile_gate_logits.argtypes = [vp] * 7
     lib.smile_route_bilevel.argtypes = [vp] * 19
     lib.smile_dispatch.argtypes = [vp] * 7
+    lib.smile_dispatch_hop1.argtypes = [vp, vp, vp, vp, i32, vp, vp]
+    lib.smile_dispatch_hop2.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.smile_expert_ffn.argtypes = [vp] * 9
     lib.smile_expert_ffn_up.argtypes = [vp] * 6
     lib.smile_expert_ffn_down.argtypes = [vp] * 6
@@ -96,10 +98,10 @@ def smile_capacity(T: int, N: int, capacity_factor: float) -> int:
 
 
 def make_desc(T, d_model, d_ff, n_groups, m_local, capacity, dtype="bf16", act="gelu",
-              alpha=0.005, beta=0.005) -> LayerDesc:
+              alpha=0.005, beta=0.005, group_capacity=0) -> LayerDesc:
     return LayerDesc(int(T), int(d_model), int(d_ff), int(n_groups), int(m_local), int(capacity),
                      DTYPE[dtype] if isinstance(dtype, str) else int(dtype),
-                     ACT[act] if isinstance(act, str) else int(act), float(alpha), float(beta))
+                     ACT[act] if isinstance(act, str) else int(act), float(alpha), float(beta), int(group_capacity))
 
 
 def smile_validate_desc(desc: LayerDesc) -> int:
@@ -185,6 +187,16 @@ def smile_route_bilevel(ctx: Ctx, logits_inter, logits_intra, bias_inter, bias_i
 def smile_dispatch(ctx: Ctx, x, group_idx, local_idx, slot, xe, stream=None):
     _check(load().smile_dispatch(ctx.handle, _ptr(x), _ptr(group_idx), _ptr(local_idx), _ptr(slot), _ptr(xe),
                                  _stream(stream)), "smile_dispatch")
+
+
+def smile_dispatch_hop1(ctx: Ctx, x, group_idx, pos_in_group, group_rows, xg, stream=None):
+    _check(load().smile_dispatch_hop1(ctx.handle, _ptr(x), _ptr(group_idx), _ptr(pos_in_group), int(group_rows),
+                                      _ptr(xg), _stream(stream)), "smile_dispatch_hop1")
+
+
+def smile_dispatch_hop2(ctx: Ctx, xg, group_idx, local_idx, pos_in_group, slot, group_rows, xe, stream=None):
+    _check(load().smile_dispatch_hop2(ctx.handle, _ptr(xg), _ptr(group_idx), _ptr(local_idx), _ptr(pos_in_group),
+                                      _ptr(slot), int(group_rows), _ptr(xe), _stream(stream)), "smile_dispatch_hop2")
 
 
 def smile_expert_ffn(ctx: Ctx, xe, kept_count, w1, b1, w2, b2, ye, stream=None):

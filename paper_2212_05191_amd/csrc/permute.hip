@@ -56,6 +56,36 @@ __global__ __launch_bounds__(kThreads) void dispatch_kernel(
     move_row<LPR>(x + (size_t)rl.t * ppr, xe + row * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
 }
 
+// First hop alone: xg[g*rows + pos_in_group] <- x[t] while the group's buffer has a row for it.
+template <int LPR>
+__global__ __launch_bounds__(kThreads) void dispatch_hop1_kernel(
+    const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ pos_in_group,
+    u32x4 *__restrict__ xg, int T, int ppr, int rows)
+{
+    const RowLanes<LPR> rl;
+    if (rl.t >= T) return;
+    const int pos = pos_in_group[rl.t];
+    if (pos < 0 || pos >= rows) return;
+    const size_t row = (size_t)group_idx[rl.t] * rows + pos;
+    move_row<LPR>(x + (size_t)rl.t * ppr, xg + row * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
+}
+
+// Second hop alone: xe[(g*m+l)*C + slot] <- xg[g*rows + pos_in_group] for kept tokens.
+template <int LPR>
+__global__ __launch_bounds__(kThreads) void dispatch_hop2_kernel(
+    const u32x4 *__restrict__ xg, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ pos_in_group, const int32_t *__restrict__ slot, u32x4 *__restrict__ xe,
+    int T, int ppr, int m, int C, int rows)
+{
+    const RowLanes<LPR> rl;
+    if (rl.t >= T) return;
+    const int sl = slot[rl.t], pos = pos_in_group[rl.t];
+    if (sl < 0 || sl >= C || pos < 0 || pos >= rows) return;
+    const int g = group_idx[rl.t];
+    const size_t src = (size_t)g * rows + pos, dst = (size_t)(g * m + local_idx[rl.t]) * C + sl;
+    move_row<LPR>(xg + src * ppr, xe + dst * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
+}
+
 // Dispatch fused with the last routing step (the chained forward pass): every thread derives the
 // token's final slot from the workspace (block offset of its expert + rank inside the block,
 // dropped at or beyond C); the thread moving piece 0 of a token also writes slot / pos_in_group.
@@ -188,6 +218,30 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
                                              group_idx, local_idx, slot, static_cast<u32x4 *>(xe), d.T, ppr, d.m_local,
                                              d.capacity));
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch_hop1(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
+                                const int32_t *pos_in_group, int group_rows, void *xg, hipStream_t s)
+{
+    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int lpr = lanes_per_row(ppr);
+    const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
+    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop1_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
+                                             group_idx, pos_in_group, static_cast<u32x4 *>(xg), d.T, ppr, group_rows));
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const int32_t *group_idx,
+                                const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
+                                int group_rows, void *xe, hipStream_t s)
+{
+    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int lpr = lanes_per_row(ppr);
+    const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
+    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop2_kernel<L>, grid, block, 0, s,
+                                             static_cast<const u32x4 *>(xg), group_idx, local_idx, pos_in_group, slot,
+                                             static_cast<u32x4 *>(xe), d.T, ppr, d.m_local, d.capacity, group_rows));
     return hipGetLastError();
 }
 

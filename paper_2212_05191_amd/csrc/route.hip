@@ -12,6 +12,11 @@
 //   route_finalize one thread per token: global rank = block offset + in-block rank; capacity cut.
 //                  (The chained forward pass skips this kernel and does the same inside dispatch.)
 //
+// With a group capacity (a first-hop buffer of Cg rows per group, Section 3.2.3) two more kernels run
+// between the scan and the last step: route_first_hop recomputes the in-block expert ranks over the
+// tokens whose stage-1 position is below Cg only (the others get a rank no capacity admits), and
+// route_scan_experts scans the new per-block expert histograms.
+//
 // Everything that decides an integer is integer arithmetic or an fp32 compare of the caller's logits,
 // so the result depends only on the logits and the token order, never on the launch geometry.  No
 // atomics order, no inter-workgroup waiting, no memory that must be cleared beforehand.
@@ -272,6 +277,57 @@ __global__ __launch_bounds__(64 * kScanWaves) void route_scan_kernel(
     }
 }
 
+// Group capacity, step 1: tokens whose stage-1 position (block offset of the group + in-block
+// position) reaches Cg are dropped at the first hop.  The in-block expert ranks and the per-block
+// expert histograms are rebuilt over the remaining tokens, overwriting those of route_decide (whose
+// totals the first scan has already turned into expert_count).
+__global__ __launch_bounds__(kRouteBlock) void route_first_hop_kernel(
+    int T, int n, int m, int Cg, int bits_N,
+    const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ block_group_off, const int32_t *__restrict__ pos_in_block,
+    int32_t *__restrict__ rank_in_block, int32_t *__restrict__ block_expert_hist)
+{
+    extern __shared__ int32_t hist[];   // [N]
+    const int N = n * m;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int t = b * kRouteBlock + tid;
+    for (int i = tid; i < N; i += kRouteBlock) hist[i] = 0;
+    int e = 0;
+    bool through = false;
+    if (t < T) {
+        const int g = group_idx[t];
+        e = g * m + local_idx[t];
+        through = block_group_off[(size_t)b * n + g] + pos_in_block[t] < Cg;
+    }
+    __syncthreads();
+    const unsigned long long me = match_any(e, bits_N, through);
+    const unsigned long long lt = lanemask_lt();
+    const int lane = __lane_id();
+    const int wave = tid >> 6;
+    for (int w = 0; w < kRouteBlock / 64; ++w) {
+        if (wave == w && through) {
+            const int base = hist[e];
+            rank_in_block[t] = base + __popcll(me & lt);
+            if (63 - __clzll(me) == lane) hist[e] = base + __popcll(me);
+        }
+        __syncthreads();
+    }
+    if (t < T && !through) rank_in_block[t] = kHop1Dropped;
+    for (int i = tid; i < N; i += kRouteBlock) block_expert_hist[(size_t)b * N + i] = hist[i];
+}
+
+// Group capacity, step 2: block offsets of the rebuilt expert histograms; kept_count = tokens that
+// reached the expert, cut at C.
+__global__ __launch_bounds__(64 * kScanWaves) void route_scan_experts_kernel(
+    int B, int N, int C, int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ kept_count)
+{
+    const int w = blockIdx.x * kScanWaves + (threadIdx.x >> 6);
+    if (w >= N) return;
+    const int total = wave_scan_column(block_expert_hist, B, N, w);
+    if ((threadIdx.x & 63) == 0) kept_count[w] = min(total, C);
+}
+
 __global__ __launch_bounds__(kRouteBlock) void route_finalize_kernel(
     int T, int n, int m, int C,
     const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
@@ -319,7 +375,19 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                        m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
                        group_count, local_count, expert_count, kept_count, p_sum, q_sum);
     err = hipGetLastError();
-    if (err != hipSuccess || !finalize) return err;
+    if (err != hipSuccess) return err;
+    if (d.group_capacity > 0) {
+        hipLaunchKernelGGL(route_first_hop_kernel, dim3(B), dim3(kRouteBlock), sizeof(int32_t) * (size_t)N, s, d.T, n, m,
+                           d.group_capacity, ceil_log2(N), group_idx, local_idx, ws.block_group_hist, ws.pos_in_block,
+                           ws.rank_in_block, ws.block_expert_hist);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(route_scan_experts_kernel, dim3((N + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0,
+                           s, B, N, d.capacity, ws.block_expert_hist, kept_count);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    if (!finalize) return err;
     hipLaunchKernelGGL(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,
                        local_idx, ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block,
                        pos_in_group, slot);

@@ -91,6 +91,8 @@ smile_status smile_validate_desc(const smile_layer_desc *desc)
     const int64_t widest = d.d_model > d.d_ff ? d.d_model : d.d_ff;
     if ((double)N * d.capacity * (double)widest >= 1099511627776.0) return SMILE_BAD_SHAPE;
     if (!std::isfinite(d.alpha) || !std::isfinite(d.beta)) return SMILE_BAD_SHAPE;
+    if (d.group_capacity < 0 || (d.group_capacity > 0 && (d.T > (1 << 30) || d.capacity >= (1 << 30))))
+        return SMILE_BAD_SHAPE;
     return SMILE_OK;
 }
 
@@ -192,6 +194,26 @@ smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_
 {
     if (!ctx || bad(x) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(xe)) return SMILE_INVALID_ARG;
     return from_hip(launch_dispatch(ctx->desc, x, group_idx, local_idx, slot, xe, static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_dispatch_hop1(smile_ctx *ctx, const void *x, const int32_t *group_idx,
+                                 const int32_t *pos_in_group, int32_t group_rows, void *xg, void *stream)
+{
+    if (!ctx || bad(x) || bad(group_idx) || bad(pos_in_group) || bad(xg)) return SMILE_INVALID_ARG;
+    if (group_rows < 1 || (int64_t)group_rows * ctx->desc.n_groups >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
+    return from_hip(launch_dispatch_hop1(ctx->desc, x, group_idx, pos_in_group, group_rows, xg,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_dispatch_hop2(smile_ctx *ctx, const void *xg, const int32_t *group_idx,
+                                 const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
+                                 int32_t group_rows, void *xe, void *stream)
+{
+    if (!ctx || bad(xg) || bad(group_idx) || bad(local_idx) || bad(pos_in_group) || bad(slot) || bad(xe))
+        return SMILE_INVALID_ARG;
+    if (group_rows < 1 || (int64_t)group_rows * ctx->desc.n_groups >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
+    return from_hip(launch_dispatch_hop2(ctx->desc, xg, group_idx, local_idx, pos_in_group, slot, group_rows, xe,
+                                         static_cast<hipStream_t>(stream)));
 }
 
 smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *kept_count,

@@ -12,6 +12,10 @@ namespace smile {
 // tokens handled by one workgroup of the routing kernels
 constexpr int kRouteBlock = 256;
 
+// in-block rank given to a token dropped at the first hop (group capacity): any block offset added to
+// it stays at or above every legal capacity and below 2^31 (T <= 2^30 is enforced with a group capacity)
+constexpr int32_t kHop1Dropped = 1 << 30;
+
 struct Workspace {
     // routing: per-block histograms turned into exclusive block offsets by the scan kernel
     int32_t *block_expert_hist;   // [B][N]
@@ -91,6 +95,13 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
 
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s);
+
+// the same move in the two hops of Section 3.2.3 through a group buffer xg[n, group_rows, d]
+hipError_t launch_dispatch_hop1(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
+                                const int32_t *pos_in_group, int group_rows, void *xg, hipStream_t s);
+hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const int32_t *group_idx,
+                                const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
+                                int group_rows, void *xe, hipStream_t s);
 
 // dispatch fused with the last routing step: computes pos_in_group / slot from the workspace ranks
 // and block offsets, writes them, and moves the rows; loss != nullptr: one wave also evaluates Eq. 4

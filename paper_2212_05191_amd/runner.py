@@ -34,7 +34,7 @@ class GpuLayer:
         self.cfg = cfg
         self.device = device
         self.desc = B.make_desc(cfg.T, cfg.d_model, cfg.d_ff, cfg.n_groups, cfg.m_local, cfg.capacity,
-                                cfg.dtype, cfg.act, alpha, beta)
+                                cfg.dtype, cfg.act, alpha, beta, cfg.group_capacity)
         self.x = to_device(wl.gen_tokens(cfg), cfg.dtype, device)
         wi, wq = wl.gen_router_weights(cfg)
         self.w_inter, self.w_intra = to_device(wi, cfg.dtype, device), to_device(wq, cfg.dtype, device)

@@ -45,6 +45,7 @@ class LayerConfig:
     act: str          # "relu" or "gelu"
     skew: bool = False  # add routing biases (Zipf inter-group, Gaussian per-expert)
     seed: int = 0
+    group_capacity: int = 0   # rows of each group's first-hop buffer; 0 = no limit
 
     @property
     def N(self) -> int:
@@ -145,6 +146,7 @@ def gen_routing_biases(cfg: LayerConfig) -> tuple[np.ndarray | None, np.ndarray 
 
 
 def small_config(name: str, T: int, d_model: int, d_ff: int, n: int, m: int, capacity: int,
-                 dtype: str = "f32", act: str = "relu", skew: bool = False, seed: int = 100) -> LayerConfig:
-    """An ad-hoc configuration for tests (capacity given as an integer)."""
-    return LayerConfig(name, T, d_model, d_ff, n, m, float("nan"), capacity, dtype, act, skew, seed)
+                 dtype: str = "f32", act: str = "relu", skew: bool = False, seed: int = 100,
+                 group_capacity: int = 0) -> LayerConfig:
+    """An ad-hoc configuration for tests (capacities given as integers)."""
+    return LayerConfig(name, T, d_model, d_ff, n, m, float("nan"), capacity, dtype, act, skew, seed, group_capacity)

@@ -50,7 +50,7 @@ def check_logits_and_routing(cfg, out, x, wi, wq, bi, bq):
     assert normwise(out["logits_inter"], li) <= tol, "inter logits"
     assert normwise(out["logits_intra"], lq) <= tol, "intra logits"
 
-    r = oracle.route(out["logits_inter"], out["logits_intra"], cfg.capacity, bi, bq)
+    r = oracle.route(out["logits_inter"], out["logits_intra"], cfg.capacity, bi, bq, cfg.group_capacity)
     for name in ("group_idx", "local_idx", "pos_in_group", "slot", "group_count", "local_count",
                  "expert_count", "kept_count"):
         np.testing.assert_array_equal(out[name], getattr(r, name), err_msg=name)
@@ -63,7 +63,7 @@ def check_logits_and_routing(cfg, out, x, wi, wq, bi, bq):
     np.testing.assert_allclose(out["loss3"], loss, rtol=1e-5, err_msg="loss")
 
     # (iv) independent oracle run: differences only at near-ties
-    ri = oracle.route(li, lq, cfg.capacity, bi, bq)
+    ri = oracle.route(li, lq, cfg.capacity, bi, bq, cfg.group_capacity)
     diff = np.nonzero((ri.group_idx != r.group_idx) | (ri.local_idx != r.local_idx))[0]
     for t in diff:
         a = li[t] + (bi if bi is not None else 0)

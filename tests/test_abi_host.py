@@ -58,6 +58,18 @@ def test_validate_desc_accepts_the_five_configs():
         d = B.make_desc(cfg.T, cfg.d_model, cfg.d_ff, cfg.n_groups, cfg.m_local, cfg.capacity, cfg.dtype, cfg.act)
         assert B.smile_validate_desc(d) == B.OK
         assert B.smile_workspace_bytes(d) > 0
+        d.group_capacity = 7
+        assert B.smile_validate_desc(d) == B.OK
+
+
+def test_desc_layout_matches_the_header():
+    """The ctypes mirror has the fields of the C struct, in the header's order (all 4-byte members)."""
+    text = open(os.path.join(ROOT, "include", "smile.h")).read()
+    body = re.search(r"typedef struct smile_layer_desc \{(.*?)\} smile_layer_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = re.findall(r"(?:int32_t|float)\s+(\w+)\s*;", body)
+    assert names == [k for k, _ in B.LayerDesc._fields_]
+    assert C.sizeof(B.LayerDesc) == 4 * len(names)
 
 
 @pytest.mark.parametrize("kw,status", [
@@ -67,7 +79,7 @@ def test_validate_desc_accepts_the_five_configs():
     (dict(n_groups=2048), B.BAD_SHAPE), (dict(n_groups=128, m_local=64), B.BAD_SHAPE),
     (dict(capacity=2 ** 30, n_groups=4), B.BAD_SHAPE),
     (dict(dtype=7), B.UNSUPPORTED), (dict(act=3), B.UNSUPPORTED),
-    (dict(alpha=float("inf")), B.BAD_SHAPE),
+    (dict(alpha=float("inf")), B.BAD_SHAPE), (dict(group_capacity=-1), B.BAD_SHAPE),
 ])
 def test_validate_desc_rejects(kw, status):
     assert B.smile_validate_desc(_desc(**kw)) == status
@@ -121,6 +133,11 @@ def test_entry_points_reject_bad_pointers_before_any_launch():
         mis[2] = p + 8      # optional bias given but misaligned
         assert lib.smile_route_bilevel(h, *mis, None) == B.INVALID_ARG
         assert lib.smile_dispatch(h, p, p, p, None, p, None) == B.INVALID_ARG
+        assert lib.smile_dispatch_hop1(h, p, p, None, 8, p, None) == B.INVALID_ARG
+        assert lib.smile_dispatch_hop1(h, p, p, p, 0, p, None) == B.BAD_SHAPE
+        assert lib.smile_dispatch_hop1(h, p, p, p, 2 ** 30, p, None) == B.BAD_SHAPE
+        assert lib.smile_dispatch_hop2(h, p, p, p, p, p, 8, p + 4, None) == B.INVALID_ARG
+        assert lib.smile_dispatch_hop2(h, p, p, p, p, p, -1, p, None) == B.BAD_SHAPE
         assert lib.smile_expert_ffn(h, p, None, p, None, p, None, p, None) == B.INVALID_ARG
         assert lib.smile_expert_ffn(h, p, p, p, p + 2, p, None, p, None) == B.INVALID_ARG
         assert lib.smile_combine(h, p, p, p, p, None, p, None) == B.INVALID_ARG

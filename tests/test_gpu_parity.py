@@ -2,6 +2,7 @@
 inputs.  Small / medium shapes are compared element by element; the full benchmark configurations
 are compared completely for routing and dispatch and on sampled rows for the expert FFN / combine.
 """
+import dataclasses
 import os
 import sys
 
@@ -69,6 +70,13 @@ SMALL = [
     wl.small_config("max_experts", 20000, 64, 64, 64, 64, 8, "bf16", "gelu", seed=27),
     wl.small_config("capacity_above_T", 700, 128, 192, 2, 2, 1000, "bf16", "gelu", seed=28),
     wl.small_config("f32_wider", 2100, 256, 512, 3, 3, 250, "f32", "gelu", seed=29),
+    # a first-hop buffer per group as well (Section 3.2.3): tight, tight with skewed groups over many routing
+    # blocks, and too loose to matter
+    wl.small_config("group_cap_f32", 1500, 64, 128, 3, 4, 100, "f32", "relu", seed=30, group_capacity=300),
+    wl.small_config("group_cap_bf16_skew", 6000, 128, 192, 4, 8, 150, "bf16", "gelu", skew=True, seed=31,
+                    group_capacity=1100),
+    wl.small_config("group_cap_loose", 900, 64, 64, 2, 3, 120, "bf16", "gelu", seed=32, group_capacity=900),
+    wl.small_config("group_cap_one_row", 300, 64, 64, 5, 2, 4, "bf16", "relu", seed=33, group_capacity=1),
 ]
 
 
@@ -82,8 +90,8 @@ def test_small_shapes_full_parity(torch_cuda, cfg):
         layer.close()
 
 
-def test_chained_entry_point_equals_step_by_step(torch_cuda):
-    cfg = SMALL[3]
+@pytest.mark.parametrize("cfg", [SMALL[3], SMALL[17]], ids=lambda c: c.name)
+def test_chained_entry_point_equals_step_by_step(torch_cuda, cfg):
     a = _run(cfg, "steps")
     b = _run(cfg, "chained", own_workspace=True)
     try:
@@ -98,7 +106,7 @@ def test_chained_entry_point_equals_step_by_step(torch_cuda):
         b.close()
 
 
-FUSED_CASES = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[6], SMALL[10],
+FUSED_CASES = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[6], SMALL[10], SMALL[16], SMALL[17], SMALL[19],
                wl.small_config("fused_ragged", 4099, 128, 256, 4, 8, 100, "bf16", "gelu", skew=True, seed=26)]
 
 
@@ -137,6 +145,45 @@ def test_fused_entry_point_full_size(torch_cuda):
             assert bool((a.buf.slot == slot_ref).all()) and bool((a.buf.loss3 == loss_ref).all()), name
         finally:
             a.close()
+
+
+@pytest.mark.parametrize("cfg", [SMALL[3], SMALL[16], SMALL[17]], ids=lambda c: c.name)
+def test_two_hop_dispatch(torch_cuda, cfg):
+    """The dispatch as the two hops of Section 3.2.3 through a materialised group buffer: hop 1 against the
+    oracle's, hop 2 against the one-hop move (bit-exact copies)."""
+    torch = torch_cuda
+    layer = _run(cfg)
+    try:
+        out = parity.fetch(layer)
+        x = parity.host_inputs(cfg)[0]
+        rows = cfg.group_capacity if cfg.group_capacity else int(out["group_count"].max())
+        b = layer.buf
+        xg = torch.full((cfg.n_groups, rows, cfg.d_model), -5.0, dtype=layer.x.dtype, device=layer.x.device)
+        xe2 = torch.full_like(b.xe, -9.0)
+        B.smile_dispatch_hop1(layer.ctx, layer.x, b.group_idx, b.pos_in_group, rows, xg)
+        B.smile_dispatch_hop2(layer.ctx, xg, b.group_idx, b.local_idx, b.pos_in_group, b.slot, rows, xe2)
+        torch.cuda.synchronize()
+        from paper_2212_05191_amd.runner import to_host
+        want = oracle.dispatch_stage1(x, out["group_idx"], out["pos_in_group"], cfg.n_groups, rows, fill=-5.0)
+        np.testing.assert_array_equal(to_host(xg), want)
+        mask = np.arange(cfg.capacity)[None, :] < out["kept_count"][:, None]
+        got = to_host(xe2)
+        np.testing.assert_array_equal(got[mask], out["xe"][mask])
+        assert np.all(got[~mask] == -9.0), "rows beyond kept_count must stay untouched"
+        want2 = oracle.dispatch_stage2(want, out["group_idx"], out["local_idx"], out["pos_in_group"], out["slot"],
+                                       cfg.m_local, cfg.capacity, fill=-9.0)
+        np.testing.assert_array_equal(got, want2)
+        # a group buffer that is too short drops the late tokens at hop 1 and never reads beyond it at hop 2
+        short = max(1, rows // 2)
+        xg_s = torch.full((cfg.n_groups, short, cfg.d_model), -5.0, dtype=layer.x.dtype, device=layer.x.device)
+        B.smile_dispatch_hop1(layer.ctx, layer.x, b.group_idx, b.pos_in_group, short, xg_s)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(
+            to_host(xg_s), oracle.dispatch_stage1(x, out["group_idx"], out["pos_in_group"], cfg.n_groups, short, fill=-5.0))
+        with pytest.raises(B.SmileError):
+            B.smile_dispatch_hop1(layer.ctx, layer.x, b.group_idx, b.pos_in_group, 0, xg)
+    finally:
+        layer.close()
 
 
 def test_repeated_calls_are_bit_identical(torch_cuda):
@@ -200,9 +247,13 @@ def test_cfg2_full_parity(torch_cuda):
         layer.close()
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5", "t2_48b"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5", "t2_48b", "cfg5_group_cap"])
 def test_full_size_configs_sampled_parity(torch_cuda, name):
-    cfg = wl.get_config(name)
+    if name == "cfg5_group_cap":
+        # cfg5 with a first-hop buffer of 1.25 x the mean group load: its Zipf-skewed groups overflow it
+        cfg = dataclasses.replace(wl.get_config("cfg5"), name=name, group_capacity=2560)
+    else:
+        cfg = wl.get_config(name)
     layer = _run(cfg, "chained", workers=16)
     try:
         info = parity.check_sampled(cfg, layer)
