@@ -1,4 +1,4 @@
-"""CPU oracle of the SMILE bi-level MoE layer forward pass (test infrastructure only).
+"""CPU oracle of the SMILE bi-level MoE layer (forward pass and its derivative) (test infrastructure only).
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
 this package.  It shares no code with the HIP library.
@@ -16,6 +16,12 @@ from .oracle import (  # noqa: F401
     combine,
     aux_loss,
     layer_forward,
+    combine_backward,
+    route_backward,
+    expert_ffn_backward,
+    dispatch_backward,
+    gate_weights_backward,
+    layer_backward,
     threads,
     RouteResult,
 )

@@ -210,3 +210,87 @@ def layer_forward(x, w_inter, w_intra, w1, w2, capacity_rows: int, act: str, dty
     y = combine(ye, r.group_idx, r.local_idx, r.slot, r.gate, m, dtype)
     loss = aux_loss(r.group_count, r.local_count, r.p_sum, r.q_sum, np.shape(x)[0], alpha, beta)
     return dict(logits_inter=li, logits_intra=lq, route=r, xe=xe, ye=ye, y=y, loss=loss)
+
+
+# ---------------------------------------------------------------- backward pass
+
+def combine_backward(dy, ye, group_idx, local_idx, slot, gate, m: int, dtype: str, fill: float = 0.0):
+    dy, ye = _f32(dy), _f32(ye)
+    N, Cap, d = ye.shape
+    T = dy.shape[0]
+    dye = np.full((N, Cap, d), fill, np.float32)
+    dgate = np.empty(T, np.float64)
+    _load().smile_oracle_combine_backward(_p(dy), _p(ye), _p(_i32(group_idx)), _p(_i32(local_idx)), _p(_i32(slot)),
+                                          _p(_f64(gate)), C.c_int32(T), C.c_int32(d), C.c_int32(m), C.c_int32(Cap),
+                                          C.c_int32(_DTYPE[dtype]), _p(dye), _p(dgate))
+    return dye, dgate
+
+
+def route_backward(logits_inter, logits_intra, group_idx, local_idx, dgate, group_count, local_count,
+                   alpha: float, beta: float, dloss: float = 1.0, bias_inter=None, bias_intra=None):
+    li, lq = _f32(logits_inter), _f32(logits_intra)
+    T, n = li.shape
+    m = lq.shape[1]
+    bi = None if bias_inter is None else _f32(bias_inter).reshape(n)
+    bq = None if bias_intra is None else _f32(bias_intra).reshape(n, m)
+    dlp = np.empty((T, n), np.float64)
+    dlq = np.empty((T, m), np.float64)
+    _load().smile_oracle_route_backward(_p(li), _p(lq), _p(bi), _p(bq), _p(_i32(group_idx)), _p(_i32(local_idx)),
+                                        _p(_f64(dgate)), _p(_i32(group_count)), _p(_i32(local_count)),
+                                        C.c_int32(T), C.c_int32(n), C.c_int32(m), C.c_double(alpha), C.c_double(beta),
+                                        C.c_double(dloss), _p(dlp), _p(dlq))
+    return dlp, dlq
+
+
+def expert_ffn_backward(xe, kept_count, w1, w2, dye, act: str, dtype: str, fill: float = 0.0):
+    xe, w1, w2, dye = _f32(xe), _f32(w1), _f32(w2), _f32(dye)
+    N, Cap, d = xe.shape
+    F = w1.shape[1]
+    assert w1.shape == (N, F, d) and w2.shape == (N, d, F) and dye.shape == xe.shape
+    kept = _i32(kept_count)
+    dxe = np.full((N, Cap, d), fill, np.float32)
+    dw1 = np.empty((N, F, d), np.float32)
+    dw2 = np.empty((N, d, F), np.float32)
+    _load().smile_oracle_expert_ffn_backward(_p(xe), _p(kept), _p(w1), _p(w2), _p(dye), C.c_int32(N), C.c_int32(Cap),
+                                             C.c_int32(d), C.c_int32(F), C.c_int32(_ACT[act]),
+                                             C.c_int32(_DTYPE[dtype]), _p(dxe), _p(dw1), _p(dw2))
+    return dxe, dw1, dw2
+
+
+def dispatch_backward(dxe, group_idx, local_idx, slot, dlp, dlq, w_inter, w_intra, dtype: str):
+    dxe, wi, wq = _f32(dxe), _f32(w_inter), _f32(w_intra)
+    N, Cap, d = dxe.shape
+    n, m = wi.shape[0], wq.shape[0]
+    g = _i32(group_idx)
+    T = g.shape[0]
+    dx = np.empty((T, d), np.float32)
+    _load().smile_oracle_dispatch_backward(_p(dxe), _p(g), _p(_i32(local_idx)), _p(_i32(slot)), _p(_f64(dlp)),
+                                           _p(_f64(dlq)), _p(wi), _p(wq), C.c_int32(T), C.c_int32(d), C.c_int32(n),
+                                           C.c_int32(m), C.c_int32(Cap), C.c_int32(_DTYPE[dtype]), _p(dx))
+    return dx
+
+
+def gate_weights_backward(x, dlp, dlq):
+    x, dlp, dlq = _f32(x), _f64(dlp), _f64(dlq)
+    T, d = x.shape
+    n, m = dlp.shape[1], dlq.shape[1]
+    dwi = np.empty((n, d), np.float64)
+    dwq = np.empty((m, d), np.float64)
+    _load().smile_oracle_gate_weights_backward(_p(x), _p(dlp), _p(dlq), C.c_int32(T), C.c_int32(d), C.c_int32(n),
+                                               C.c_int32(m), _p(dwi), _p(dwq))
+    return dwi, dwq
+
+
+def layer_backward(fwd: dict, x, w_inter, w_intra, w1, w2, dy, act: str, dtype: str,
+                   alpha: float = 0.005, beta: float = 0.005, dloss: float = 1.0, bias_inter=None, bias_intra=None):
+    """Chain the backward steps in reverse order of layer_forward(); `fwd` is its result."""
+    r = fwd["route"]
+    m = np.shape(w_intra)[0]
+    dye, dgate = combine_backward(dy, fwd["ye"], r.group_idx, r.local_idx, r.slot, r.gate, m, dtype)
+    dlp, dlq = route_backward(fwd["logits_inter"], fwd["logits_intra"], r.group_idx, r.local_idx, dgate,
+                              r.group_count, r.local_count, alpha, beta, dloss, bias_inter, bias_intra)
+    dxe, dw1, dw2 = expert_ffn_backward(fwd["xe"], r.kept_count, w1, w2, dye, act, dtype)
+    dx = dispatch_backward(dxe, r.group_idx, r.local_idx, r.slot, dlp, dlq, w_inter, w_intra, dtype)
+    dwi, dwq = gate_weights_backward(x, dlp, dlq)
+    return dict(dye=dye, dgate=dgate, dlp=dlp, dlq=dlq, dxe=dxe, dw1=dw1, dw2=dw2, dx=dx,
+                dw_inter=dwi, dw_intra=dwq)

@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the forward pass of one SMILE bi-level routed MoE layer.
+ * CPU oracle for one SMILE bi-level routed MoE layer: forward pass and, at the
+ * end of the file, its derivative (backward pass).
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, written-from-the-
  * paper definition of what the layer computes.  It exists so that the GPU
@@ -350,4 +351,197 @@ void smile_oracle_aux_loss(const int32_t *group_count, const int32_t *local_coun
     out3[0] = inter;
     out3[1] = intra;
     out3[2] = alpha * inter + beta * intra;
+}
+
+/* ===========================================================================
+ * Backward pass: the derivative of the forward map above.
+ *
+ * The paper trains the layer (Section 4.1) but prints no gradient formulas, so
+ * the definition is the chain rule applied to Eq. 3 and Eq. 4:
+ *     L = sum_{t,k} dy[t,k] * y[t,k]  +  dloss * (alpha*inter + beta*intra)
+ * with the discrete decisions (top-1 indices, slots, drops) and the fractions
+ * f of Eq. 4 held constant, as for the Switch loss the paper builds on
+ * (Section 2).  The functions take the steps of the forward pass in reverse.
+ * Values that the layer would store in its storage type are rounded there
+ * (dye, the gradient at the pre-activation, dxe, dx, the expert weight
+ * gradients); every sum is accumulated in double.
+ * =========================================================================== */
+
+/* Eq. 3 backwards: y[t] = gate_t * ye[row(t)] for a kept token, so
+ *   dye[row(t), :] = gate_t * dy[t, :]      (rounded to the storage type)
+ *   dgate[t]       = sum_k dy[t,k] * ye[row(t),k]
+ * and a dropped token (y[t] = 0) sends nothing back: dgate[t] = 0.  Rows of
+ * dye that no token owns keep the caller's values. */
+void smile_oracle_combine_backward(const float *dy, const float *ye, const int32_t *group_idx,
+                                   const int32_t *local_idx, const int32_t *slot, const double *gate,
+                                   int32_t T, int32_t d, int32_t m, int32_t C, int32_t dtype,
+                                   float *dye, double *dgate)
+{
+    for (int32_t t = 0; t < T; ++t) {
+        dgate[t] = 0.0;
+        if (slot[t] < 0) continue;
+        size_t row = ((size_t)(group_idx[t] * m + local_idx[t]) * C + (size_t)slot[t]);
+        double s = 0.0;
+        for (int32_t k = 0; k < d; ++k) {
+            s += (double)dy[(size_t)t * d + k] * (double)ye[row * d + k];
+            dye[row * d + k] = (float)store_round(gate[t] * (double)dy[(size_t)t * d + k], dtype);
+        }
+        dgate[t] = s;
+    }
+}
+
+/* softmax of a biased logit row into prob[len] (same arithmetic as the forward pass) */
+static void softmax_row(const float *row, const float *bias, int32_t len, float *a, double *prob)
+{
+    for (int32_t i = 0; i < len; ++i) a[i] = bias ? row[i] + bias[i] : row[i];
+    (void)softmax_top1(a, len, prob);
+}
+
+/* Routers backwards.  With p = softmax(a), q = softmax(c) (Eq. 1), gate = p_g * q_l (Eq. 3) and
+ * Eq. 4's P_i = (1/T) sum_t p[t,i], Q_j likewise, the derivative of L with respect to the
+ * probabilities of token t is
+ *   u_i = dloss*alpha*n*f_i/T + [i == g_t] * dgate[t] * q[l_t]
+ *   v_j = dloss*beta *m*f_j/T + [j == l_t] * dgate[t] * p[g_t]
+ * and the softmax Jacobian gives the derivative with respect to the logits:
+ *   dlp[t,k] = p_k * (u_k - sum_i u_i p_i),   dlq[t,k] = q_k * (v_k - sum_j v_j q_j). */
+void smile_oracle_route_backward(const float *logits_inter, const float *logits_intra,
+                                 const float *bias_inter, const float *bias_intra,
+                                 const int32_t *group_idx, const int32_t *local_idx, const double *dgate,
+                                 const int32_t *group_count, const int32_t *local_count,
+                                 int32_t T, int32_t n, int32_t m, double alpha, double beta, double dloss,
+                                 double *dlp, double *dlq)
+{
+    int32_t len = n > m ? n : m;
+    float *a = (float *)malloc(sizeof(float) * (size_t)len);
+    double *p = (double *)malloc(sizeof(double) * (size_t)n);
+    double *q = (double *)malloc(sizeof(double) * (size_t)m);
+    double *u = (double *)malloc(sizeof(double) * (size_t)len);
+    for (int32_t t = 0; t < T; ++t) {
+        int32_t g = group_idx[t], l = local_idx[t];
+        softmax_row(logits_inter + (size_t)t * n, bias_inter, n, a, p);
+        softmax_row(logits_intra + (size_t)t * m, bias_intra ? bias_intra + (size_t)g * m : NULL, m, a, q);
+        double dot = 0.0;
+        for (int32_t i = 0; i < n; ++i) {
+            u[i] = dloss * alpha * (double)n * ((double)group_count[i] / T) / T;
+            if (i == g) u[i] += dgate[t] * q[l];
+            dot += u[i] * p[i];
+        }
+        for (int32_t i = 0; i < n; ++i) dlp[(size_t)t * n + i] = p[i] * (u[i] - dot);
+        dot = 0.0;
+        for (int32_t j = 0; j < m; ++j) {
+            u[j] = dloss * beta * (double)m * ((double)local_count[j] / T) / T;
+            if (j == l) u[j] += dgate[t] * p[g];
+            dot += u[j] * q[j];
+        }
+        for (int32_t j = 0; j < m; ++j) dlq[(size_t)t * m + j] = q[j] * (u[j] - dot);
+    }
+    free(a); free(p); free(q); free(u);
+}
+
+static double act_grad(double v, int act)
+{
+    if (act == 0) return v > 0.0 ? 1.0 : 0.0;
+    /* d/dv [v Phi(v)] = Phi(v) + v phi(v) */
+    return 0.5 * (1.0 + erf(v / sqrt(2.0))) + v * exp(-0.5 * v * v) / sqrt(2.0 * 3.14159265358979323846);
+}
+
+/* Expert FFN backwards (the E_{i,j} of Eq. 3, Section 4.1), for the rows r < kept[e] of every expert:
+ *   pre = xe . W1^T,  h = act(pre)         (recomputed; pre and h rounded to the storage type)
+ *   dh   = dye . W2                         [rows, F]
+ *   dpre = dh * act'(pre)                   (rounded to the storage type)
+ *   dxe  = dpre . W1                        [rows, d]   (rounded)
+ *   dW2[c,f] = sum_r dye[r,c] * h[r,f],   dW1[f,k] = sum_r dpre[r,f] * xe[r,k]   (rounded)
+ * Rows of dxe at or beyond kept[e] keep the caller's values; an expert without tokens gets zero
+ * weight gradients. */
+void smile_oracle_expert_ffn_backward(const float *xe, const int32_t *kept_count, const float *w1,
+                                      const float *w2, const float *dye,
+                                      int32_t N, int32_t C, int32_t d, int32_t F, int32_t act, int32_t dtype,
+                                      float *dxe, float *dw1, float *dw2)
+{
+    for (int32_t e = 0; e < N; ++e) {
+        const float *W1 = w1 + (size_t)e * F * d;
+        const float *W2 = w2 + (size_t)e * d * F;
+        const int32_t rows = kept_count[e];
+        double *h = (double *)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1) * F);
+        double *dpre = (double *)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1) * F);
+#pragma omp parallel for schedule(static)
+        for (int32_t r = 0; r < rows; ++r) {
+            const float *xr = xe + ((size_t)e * C + r) * d;
+            const float *gr = dye + ((size_t)e * C + r) * d;
+            for (int32_t f = 0; f < F; ++f) {
+                double s = 0.0;
+                for (int32_t k = 0; k < d; ++k) s += (double)xr[k] * (double)W1[(size_t)f * d + k];
+                h[(size_t)r * F + f] = store_round(act_fn(s, act), dtype);
+                double pre = store_round(s, dtype);
+                double dh = 0.0;
+                for (int32_t c = 0; c < d; ++c) dh += (double)gr[c] * (double)W2[(size_t)c * F + f];
+                dpre[(size_t)r * F + f] = store_round(dh * act_grad(pre, act), dtype);
+            }
+            float *dxr = dxe + ((size_t)e * C + r) * d;
+            for (int32_t k = 0; k < d; ++k) {
+                double s = 0.0;
+                for (int32_t f = 0; f < F; ++f) s += dpre[(size_t)r * F + f] * (double)W1[(size_t)f * d + k];
+                dxr[k] = (float)store_round(s, dtype);
+            }
+        }
+#pragma omp parallel for schedule(static)
+        for (int32_t f = 0; f < F; ++f) {
+            for (int32_t k = 0; k < d; ++k) {
+                double s = 0.0;
+                for (int32_t r = 0; r < rows; ++r) s += dpre[(size_t)r * F + f] * (double)xe[((size_t)e * C + r) * d + k];
+                dw1[((size_t)e * F + f) * d + k] = (float)store_round(s, dtype);
+            }
+        }
+#pragma omp parallel for schedule(static)
+        for (int32_t c = 0; c < d; ++c) {
+            for (int32_t f = 0; f < F; ++f) {
+                double s = 0.0;
+                for (int32_t r = 0; r < rows; ++r) s += (double)dye[((size_t)e * C + r) * d + c] * h[(size_t)r * F + f];
+                dw2[((size_t)e * d + c) * F + f] = (float)store_round(s, dtype);
+            }
+        }
+        free(h);
+        free(dpre);
+    }
+}
+
+/* Dispatch and router logits backwards: a token's input reached the output through its expert
+ * (xe[row(t)] = x[t], kept tokens only) and through the two routers (logits = W x):
+ *   dx[t,:] = dxe[row(t),:] (0 if dropped) + sum_i dlp[t,i] W_p[i,:] + sum_j dlq[t,j] W_q[j,:]
+ * rounded once to the storage type. */
+void smile_oracle_dispatch_backward(const float *dxe, const int32_t *group_idx, const int32_t *local_idx,
+                                    const int32_t *slot, const double *dlp, const double *dlq,
+                                    const float *w_inter, const float *w_intra,
+                                    int32_t T, int32_t d, int32_t n, int32_t m, int32_t C, int32_t dtype, float *dx)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t t = 0; t < T; ++t) {
+        for (int32_t k = 0; k < d; ++k) {
+            double s = 0.0;
+            if (slot[t] >= 0)
+                s = (double)dxe[(((size_t)(group_idx[t] * m + local_idx[t]) * C + (size_t)slot[t])) * d + k];
+            for (int32_t i = 0; i < n; ++i) s += dlp[(size_t)t * n + i] * (double)w_inter[(size_t)i * d + k];
+            for (int32_t j = 0; j < m; ++j) s += dlq[(size_t)t * m + j] * (double)w_intra[(size_t)j * d + k];
+            dx[(size_t)t * d + k] = (float)store_round(s, dtype);
+        }
+    }
+}
+
+/* Router weights backwards (logits = W x): dW_p[i,:] = sum_t dlp[t,i] x[t,:], dW_q[j,:] likewise. */
+void smile_oracle_gate_weights_backward(const float *x, const double *dlp, const double *dlq,
+                                        int32_t T, int32_t d, int32_t n, int32_t m,
+                                        double *dw_inter, double *dw_intra)
+{
+    for (int32_t i = 0; i < n; ++i)
+        for (int32_t k = 0; k < d; ++k) {
+            double s = 0.0;
+            for (int32_t t = 0; t < T; ++t) s += dlp[(size_t)t * n + i] * (double)x[(size_t)t * d + k];
+            dw_inter[(size_t)i * d + k] = s;
+        }
+    for (int32_t j = 0; j < m; ++j)
+        for (int32_t k = 0; k < d; ++k) {
+            double s = 0.0;
+            for (int32_t t = 0; t < T; ++t) s += dlq[(size_t)t * m + j] * (double)x[(size_t)t * d + k];
+            dw_intra[(size_t)j * d + k] = s;
+        }
 }
