@@ -233,6 +233,98 @@ typedef struct smile_layer_io {
  *     tokens are zeroed by the routing (6 launches, no [N,C,d] traffic). */
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * Backward pass.  The paper trains the layer (Section 4.1) and prints no gradient formulas; these
+ * entry points compute the derivative of the forward map defined above (Eq. 3 for y, Eq. 4 for the
+ * loss) by the chain rule, for
+ *     L = sum_{t,k} dy[t,k] * y[t,k] + dloss * (alpha*inter + beta*intra),
+ * with the discrete decisions (top-1 indices, slots, drops) and the fractions f of Eq. 4 held
+ * constant, as for the Switch loss of Section 2.  Gradient tensors stored in the ctx dtype (dye,
+ * dxe, dx, dw1, dw2) are rounded once from fp32; dgate, dlp, dlq, dw_inter, dw_intra are fp32.
+ * Experts with bias vectors are not covered (there is no b1 / b2 argument and no gradient for them).
+ * The steps mirror the forward ones in reverse order; the tensors "saved from the forward pass" are
+ * the outputs of the forward entry points for the same inputs.
+ * ------------------------------------------------------------------------- */
+
+/* Bytes of device scratch memory smile_expert_ffn_backward, smile_gate_weights_backward and
+ * smile_layer_backward need (recomputed activations, transposed operands, partial sums; about
+ * 5 N*C*F + 2 N*C*d + N*d*F elements).  Host-only.  The memory is the caller's, 256-byte aligned,
+ * and only used during the call's enqueued work. */
+smile_status smile_backward_workspace_bytes(const smile_layer_desc *desc, size_t *bytes);
+
+/* Eq. 3 backwards: for a kept token dye[e, slot[t], :] = gate[t] * dy[t, :] and
+ * dgate[t] = sum_k dy[t,k] * ye[e, slot[t], k]; a dropped token gives dgate[t] = 0.
+ * dy[T,d], ye[N,C,d], dye[N,C,d] in the ctx dtype; rows of dye no token owns are not written. */
+smile_status smile_combine_backward(smile_ctx *ctx, const void *dy, const void *ye, const int32_t *group_idx,
+                                    const int32_t *local_idx, const int32_t *slot, const float *gate,
+                                    void *dye, float *dgate, void *stream);
+
+/* The two routers backwards (Eq. 1 softmax, Eq. 3 gate, Eq. 4 loss).  With p, q the softmax rows of
+ * token t (biases as in smile_route_bilevel), g = group_idx[t], l = local_idx[t]:
+ *   u_i = dloss*alpha*n*group_count[i]/T^2 + [i == g] * dgate[t] * q[l],   dlp[t,k] = p_k (u_k - sum_i u_i p_i)
+ *   v_j = dloss*beta *m*local_count[j]/T^2 + [j == l] * dgate[t] * p[g],   dlq[t,k] = q_k (v_k - sum_j v_j q_j)
+ * dlp[T,n], dlq[T,m] fp32: the gradients with respect to the router logits. */
+smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, const float *logits_intra,
+                                  const float *bias_inter, const float *bias_intra,
+                                  const int32_t *group_idx, const int32_t *local_idx, const float *dgate,
+                                  const int32_t *group_count, const int32_t *local_count, float dloss,
+                                  float *dlp, float *dlq, void *stream);
+
+/* Expert FFN backwards (E_e of Eq. 3, Section 4.1, no bias vectors), rows r < kept_count[e]:
+ *   pre = xe[e] . w1[e]^T, h = act(pre)     (recomputed here, both rounded to the ctx dtype)
+ *   dpre = (dye[e] . w2[e]) * act'(pre)
+ *   dxe[e] = dpre . w1[e]                                              [N,C,d]
+ *   dw2[e][c,f] = sum_r dye[e,r,c] * h[r,f]                            [N,d,F]
+ *   dw1[e][f,k] = sum_r dpre[r,f] * xe[e,r,k]                          [N,F,d]
+ * Rows of dxe at or beyond kept_count[e] are not written; an expert without rows gets zero
+ * weight gradients. */
+smile_status smile_expert_ffn_backward(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                       const void *w1, const void *w2, const void *dye,
+                                       void *dxe, void *dw1, void *dw2,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Dispatch and router logits backwards: dx[t,:] = dxe[e, slot[t], :] (zero for a dropped token)
+ *   + sum_i dlp[t,i] * w_inter[i,:] + sum_j dlq[t,j] * w_intra[j,:], rounded once.  dx[T,d]. */
+smile_status smile_dispatch_backward(smile_ctx *ctx, const void *dxe, const int32_t *group_idx,
+                                     const int32_t *local_idx, const int32_t *slot, const float *dlp,
+                                     const float *dlq, const void *w_inter, const void *w_intra, void *dx,
+                                     void *stream);
+
+/* Router weights backwards: dw_inter[i,:] = sum_t dlp[t,i] * x[t,:], dw_intra[j,:] = sum_t dlq[t,j] * x[t,:]
+ * (fp32 [n,d] and [m,d]); summed in a fixed order, so repeated calls give identical bits. */
+smile_status smile_gate_weights_backward(smile_ctx *ctx, const void *x, const float *dlp, const float *dlq,
+                                         float *dw_inter, float *dw_intra,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* All tensors of one backward pass, for smile_layer_backward. */
+typedef struct smile_backward_io {
+    /* inputs of the forward pass */
+    const void *x, *w_inter, *w_intra, *w1, *w2;
+    const float *bias_inter, *bias_intra;            /* may be NULL */
+    /* saved from the forward pass */
+    const float *logits_inter, *logits_intra;
+    const int32_t *group_idx, *local_idx, *slot;
+    const float *gate;
+    const int32_t *group_count, *local_count, *kept_count;
+    const void *xe, *ye;
+    /* upstream gradient of y */
+    const void *dy;
+    /* intermediates (caller-allocated): dye[N,C,d], dgate[T], dlp[T,n], dlq[T,m], dxe[N,C,d] */
+    void *dye;
+    float *dgate, *dlp, *dlq;
+    void *dxe;
+    /* results */
+    void *dx;
+    float *dw_inter, *dw_intra;
+    void *dw1, *dw2;
+} smile_backward_io;
+
+/* The five backward steps in one call, in the order combine, route, expert FFN, dispatch, router
+ * weights; same results as calling them one by one.  dloss is the upstream gradient of the
+ * scalar loss of Eq. 4 (out3[2] of smile_aux_loss). */
+smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, float dloss,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

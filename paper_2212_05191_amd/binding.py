@@ -40,10 +40,20 @@ class LayerIO(C.Structure):
         "p_sum", "q_sum", "xe", "ye", "y", "loss3", "prof_up_start", "prof_up_stop")]
 
 
+class BackwardIO(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in (
+        "x", "w_inter", "w_intra", "w1", "w2", "bias_inter", "bias_intra",
+        "logits_inter", "logits_intra", "group_idx", "local_idx", "slot", "gate",
+        "group_count", "local_count", "kept_count", "xe", "ye", "dy",
+        "dye", "dgate", "dlp", "dlq", "dxe", "dx", "dw_inter", "dw_intra", "dw1", "dw2")]
+
+
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
     "smile_dispatch", "smile_dispatch_hop1", "smile_dispatch_hop2", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
+    "smile_backward_workspace_bytes", "smile_combine_backward", "smile_route_backward", "smile_expert_ffn_backward",
+    "smile_dispatch_backward", "smile_gate_weights_backward", "smile_layer_backward",
 )
 
 
@@ -79,6 +89,13 @@ def load() -> C.CDLL:
     lib.smile_combine.argtypes = [vp] * 8
     lib.smile_aux_loss.argtypes = [vp] * 7
     lib.smile_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]
+    lib.smile_backward_workspace_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
+    lib.smile_combine_backward.argtypes = [vp] * 10
+    lib.smile_route_backward.argtypes = [vp] * 10 + [C.c_float, vp, vp, vp]
+    lib.smile_expert_ffn_backward.argtypes = [vp] * 10 + [C.c_size_t, vp]
+    lib.smile_dispatch_backward.argtypes = [vp] * 11
+    lib.smile_gate_weights_backward.argtypes = [vp] * 7 + [C.c_size_t, vp]
+    lib.smile_layer_backward.argtypes = [vp, C.POINTER(BackwardIO), C.c_float, vp, C.c_size_t, vp]
     for name in EXPORTS[3:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -226,6 +243,96 @@ def smile_aux_loss(ctx: Ctx, group_count, local_count, p_sum, q_sum, out3, strea
 
 def smile_layer_forward(ctx: Ctx, io: LayerIO, stream=None):
     _check(load().smile_layer_forward(ctx.handle, C.byref(io), _stream(stream)), "smile_layer_forward")
+
+
+# ------------------------------------------------------------------ backward pass
+
+def smile_backward_workspace_bytes(desc: LayerDesc) -> int:
+    out = C.c_size_t(0)
+    _check(load().smile_backward_workspace_bytes(C.byref(desc), C.byref(out)), "smile_backward_workspace_bytes")
+    return int(out.value)
+
+
+def smile_combine_backward(ctx: Ctx, dy, ye, group_idx, local_idx, slot, gate, dye, dgate, stream=None):
+    _check(load().smile_combine_backward(ctx.handle, _ptr(dy), _ptr(ye), _ptr(group_idx), _ptr(local_idx), _ptr(slot),
+                                         _ptr(gate), _ptr(dye), _ptr(dgate), _stream(stream)), "smile_combine_backward")
+
+
+def smile_route_backward(ctx: Ctx, logits_inter, logits_intra, bias_inter, bias_intra, group_idx, local_idx, dgate,
+                         group_count, local_count, dloss, dlp, dlq, stream=None):
+    _check(load().smile_route_backward(ctx.handle, _ptr(logits_inter), _ptr(logits_intra), _ptr(bias_inter),
+                                       _ptr(bias_intra), _ptr(group_idx), _ptr(local_idx), _ptr(dgate),
+                                       _ptr(group_count), _ptr(local_count), float(dloss), _ptr(dlp), _ptr(dlq),
+                                       _stream(stream)), "smile_route_backward")
+
+
+def smile_expert_ffn_backward(ctx: Ctx, xe, kept_count, w1, w2, dye, dxe, dw1, dw2, workspace, stream=None):
+    _check(load().smile_expert_ffn_backward(ctx.handle, _ptr(xe), _ptr(kept_count), _ptr(w1), _ptr(w2), _ptr(dye),
+                                            _ptr(dxe), _ptr(dw1), _ptr(dw2), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "smile_expert_ffn_backward")
+
+
+def smile_dispatch_backward(ctx: Ctx, dxe, group_idx, local_idx, slot, dlp, dlq, w_inter, w_intra, dx, stream=None):
+    _check(load().smile_dispatch_backward(ctx.handle, _ptr(dxe), _ptr(group_idx), _ptr(local_idx), _ptr(slot),
+                                          _ptr(dlp), _ptr(dlq), _ptr(w_inter), _ptr(w_intra), _ptr(dx),
+                                          _stream(stream)), "smile_dispatch_backward")
+
+
+def smile_gate_weights_backward(ctx: Ctx, x, dlp, dlq, dw_inter, dw_intra, workspace, stream=None):
+    _check(load().smile_gate_weights_backward(ctx.handle, _ptr(x), _ptr(dlp), _ptr(dlq), _ptr(dw_inter),
+                                              _ptr(dw_intra), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream)),
+           "smile_gate_weights_backward")
+
+
+def smile_layer_backward(ctx: Ctx, io: BackwardIO, dloss, workspace, stream=None):
+    _check(load().smile_layer_backward(ctx.handle, C.byref(io), float(dloss), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "smile_layer_backward")
+
+
+@dataclass
+class BackwardBuffers:
+    """Intermediates and results of one backward pass as torch tensors on the GPU."""
+    dye: object
+    dgate: object
+    dlp: object
+    dlq: object
+    dxe: object
+    dx: object
+    dw_inter: object
+    dw_intra: object
+    dw1: object
+    dw2: object
+
+
+def alloc_backward_buffers(desc: LayerDesc, device="cuda:0") -> BackwardBuffers:
+    import torch
+    T, d, F, n, m, Cap = desc.T, desc.d_model, desc.d_ff, desc.n_groups, desc.m_local, desc.capacity
+    N = n * m
+    st = torch.bfloat16 if desc.dtype == DTYPE["bf16"] else torch.float32
+    f32 = torch.float32
+
+    def e(shape, dt):
+        return torch.empty(shape, dtype=dt, device=device)
+
+    return BackwardBuffers(e((N, Cap, d), st), e((T,), f32), e((T, n), f32), e((T, m), f32), e((N, Cap, d), st),
+                           e((T, d), st), e((n, d), f32), e((m, d), f32), e((N, F, d), st), e((N, d, F), st))
+
+
+def make_backward_io(x, w_inter, w_intra, w1, w2, fwd: "LayerBuffers", dy, bwd: BackwardBuffers, bias_inter=None,
+                     bias_intra=None) -> BackwardIO:
+    io = BackwardIO()
+    for k, v in dict(x=x, w_inter=w_inter, w_intra=w_intra, w1=w1, w2=w2, bias_inter=bias_inter,
+                     bias_intra=bias_intra, dy=dy).items():
+        setattr(io, k, _ptr(v))
+    for k in ("logits_inter", "logits_intra", "group_idx", "local_idx", "slot", "gate", "group_count", "local_count",
+              "kept_count", "xe", "ye"):
+        setattr(io, k, _ptr(getattr(fwd, k)))
+    for k, v in bwd.__dict__.items():
+        setattr(io, k, _ptr(v))
+    return io
 
 
 # ------------------------------------------------------------------ device buffers for one layer

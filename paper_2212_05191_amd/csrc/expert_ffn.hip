@@ -90,6 +90,7 @@ struct GemmArgs {
     const int32_t *y_rows;  // scatter: output row also goes to y_tok[y_rows[e*C + r]] * gate  (combine fused in)
     void *y_tok;            // [T][Nout]
     const float *gate;      // [T]
+    void *y2 = nullptr;     // [N][C][Nout]: the same product without the activation (DUAL kernels only)
 };
 
 // One 16-byte piece (8 bf16) times a gate: fp32 product, rounded to bf16 (nearest even) -- the same
@@ -130,7 +131,9 @@ __device__ __forceinline__ int swz(int row)
 
 // OCC: waves per SIMD the register allocation must leave room for (workgroups per CU when the
 // workgroup has 4 waves).
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT>
+// DUAL: the epilogue runs twice, storing act(product) to y and the bare product to y2 (the backward
+// pass recomputes the hidden activation and its pre-activation in one GEMM).
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT, bool DUAL = false>
 __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
 {
     constexpr int NW = WGM * WGN, NT = NW * 64;
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     const int e = lid / per_expert;
     const int rem = lid - e * per_expert;
     const int ct = rem / a.row_tiles, rt = rem - ct * a.row_tiles;
-    const int rows = min(a.kept[e], a.C);   // never trust a count beyond the buffer
+    const int rows = a.kept ? min(a.kept[e], a.C) : a.C;   // never trust a count beyond the buffer
     if (rt * BM >= rows) return;
 
     const int K = a.K, Nout = a.Nout;
@@ -285,43 +288,47 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     // row lane%32) of its 32x32 tile.  One pass per 32-row slice of the wave tiles: bias +
     // activation + rounding, 8-byte writes into a [OROWS][BN] staging tile, then row-contiguous
     // 16-byte global stores by the whole workgroup.
-    __bf16 *Y = a.y ? static_cast<__bf16 *>(a.y) + (size_t)e * a.C * Nout : nullptr;
     const int32_t *y_rows = a.y_rows ? a.y_rows + (size_t)e * a.C : nullptr;
     const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (size_t)e * Nout : nullptr;
     u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
     constexpr int OPR = BN / 8;   // 16-byte pieces per output row
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
-        __builtin_amdgcn_s_barrier();          // main-loop reads / the previous pass's stores are finished
+    for (int pass = 0; pass < (DUAL ? 2 : 1); ++pass) {
+        void *dst = pass == 0 ? a.y : a.y2;
+        __bf16 *Y = dst ? static_cast<__bf16 *>(dst) + (size_t)e * a.C * Nout : nullptr;
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
+        for (int j = 0; j < TM; ++j) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
+            __builtin_amdgcn_s_barrier();          // main-loop reads / the previous pass's stores are finished
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int lcol = wn * WN + i * 32 + 8 * q + 4 * fhi;      // column inside the tile
-                bf16x4 out;
+            for (int i = 0; i < TN; ++i) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float f = acc[i][j][4 * q + v];
-                    if (bias) f += (float)bias[min(ct * BN + lcol + v, Nout - 1)];
-                    out[v] = (__bf16)activate<ACT>(f);
+                for (int q = 0; q < 4; ++q) {
+                    const int lcol = wn * WN + i * 32 + 8 * q + 4 * fhi;      // column inside the tile
+                    bf16x4 out;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float f = acc[i][j][4 * q + v];
+                        if (bias) f += (float)bias[min(ct * BN + lcol + v, Nout - 1)];
+                        out[v] = (__bf16)(pass == 0 ? activate<ACT>(f) : f);
+                    }
+                    stg[((wm * 32 + frow) * OSTRIDE) * 2 + (lcol >> 2)] = __builtin_bit_cast(u32x2, out);
                 }
-                stg[((wm * 32 + frow) * OSTRIDE) * 2 + (lcol >> 2)] = __builtin_bit_cast(u32x2, out);
             }
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __builtin_amdgcn_s_barrier();
-        for (int id = tid; id < OROWS * OPR; id += NT) {
-            const int orow = id / OPR, piece = id - orow * OPR;
-            const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
-            const int col = ct * BN + piece * 8;
-            if (row < rows && col < Nout) {
-                const u32x4 v = lds[orow * OSTRIDE + piece];
-                if (Y) *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = v;
-                if (y_rows) {   // gate-weighted return to token order (Eq. 3), fused
-                    const int tok = y_rows[row];
-                    *reinterpret_cast<u32x4 *>(static_cast<__bf16 *>(a.y_tok) + (size_t)tok * Nout + col) =
-                        scale_bf16x8(v, a.gate[tok]);
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            for (int id = tid; id < OROWS * OPR; id += NT) {
+                const int orow = id / OPR, piece = id - orow * OPR;
+                const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
+                const int col = ct * BN + piece * 8;
+                if (row < rows && col < Nout) {
+                    const u32x4 v = lds[orow * OSTRIDE + piece];
+                    if (Y) *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = v;
+                    if (pass == 0 && y_rows) {   // gate-weighted return to token order (Eq. 3), fused
+                        const int tok = y_rows[row];
+                        *reinterpret_cast<u32x4 *>(static_cast<__bf16 *>(a.y_tok) + (size_t)tok * Nout + col) =
+                            scale_bf16x8(v, a.gate[tok]);
+                    }
                 }
             }
         }
@@ -347,6 +354,20 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
     if (act == 0) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
     else if (act == 1) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
     else launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
+    return hipGetLastError();
+}
+
+// act(product) and the bare product in one launch (tile 0 only: this is an up-projection shape)
+hipError_t launch_bf16_dual(GemmArgs a, int N, int act, hipStream_t s)
+{
+    constexpr int BM = 128, BN = 192;
+    a.row_tiles = (a.C + BM - 1) / BM;
+    a.col_tiles = (a.Nout + BN - 1) / BN;
+    a.tiles = N * a.row_tiles * a.col_tiles;
+    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
+    const dim3 grid(per_xcd * kXcds), block(256);
+    if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -394,7 +415,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
     const float *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias,
     float *__restrict__ y, const int32_t *__restrict__ kept, int C, int Nout, int K, int row_tiles, int col_tiles,
     const int32_t *__restrict__ x_rows, const int32_t *__restrict__ y_rows, float *__restrict__ y_tok,
-    const float *__restrict__ gate)
+    const float *__restrict__ gate, float *__restrict__ y2)
 {
     constexpr int BT = 64, BK = 16;
     __shared__ float xs[BK][BT + 4];
@@ -404,7 +425,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
     const int e = blockIdx.x / per_expert;
     const int rem = blockIdx.x - e * per_expert;
     const int ct = rem / row_tiles, rt = rem - ct * row_tiles;
-    const int rows = min(kept[e], C);
+    const int rows = kept ? min(kept[e], C) : C;
     if (rt * BT >= rows) return;
 
     const float *X = x + (x_rows ? (size_t)0 : (size_t)e * C * K);
@@ -450,6 +471,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
             if (col >= Nout) continue;
             float f = acc[i][j];
             if (bias) f += bias[(size_t)e * Nout + col];
+            if (y2) y2[((size_t)e * C + row) * Nout + col] = f;   // the bare product as well
             f = activate<ACT>(f);
             if (Y) Y[(size_t)row * Nout + col] = f;
             if (y_rows) y_tok[(size_t)tok * Nout + col] = f * g;
@@ -459,23 +481,39 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
 
 hipError_t launch_f32(const float *x, const float *w, const float *bias, float *y, const int32_t *kept, int N,
                       int C, int Nout, int K, int act, hipStream_t s, const int32_t *x_rows = nullptr,
-                      const int32_t *y_rows = nullptr, float *y_tok = nullptr, const float *gate = nullptr)
+                      const int32_t *y_rows = nullptr, float *y_tok = nullptr, const float *gate = nullptr,
+                      float *y2 = nullptr)
 {
     const int row_tiles = (C + 63) / 64, col_tiles = (Nout + 63) / 64;
     const dim3 grid(N * row_tiles * col_tiles), block(256);
     if (act == 0)
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<0>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate);
+                           x_rows, y_rows, y_tok, gate, y2);
     else if (act == 1)
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<1>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate);
+                           x_rows, y_rows, y_tok, gate, y2);
     else
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<2>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate);
+                           x_rows, y_rows, y_tok, gate, y2);
     return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s)
+{
+    const int act = g.act == 0 ? 0 : (g.act == 1 ? 1 : 2);
+    if (dtype == SMILE_DTYPE_BF16) {
+        if (g.K % 64 || g.Nout % 8) return hipErrorInvalidValue;
+        GemmArgs a{g.x, g.w, nullptr, g.y, g.kept, g.C, g.Nout, g.K, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, g.y2};
+        if (g.y2) return launch_bf16_dual(a, g.N, act, s);
+        return launch_bf16(a, g.N, act, pick_tile(g.N, g.C, g.Nout, g.K), s);
+    }
+    if (g.K % 4) return hipErrorInvalidValue;
+    return launch_f32(static_cast<const float *>(g.x), static_cast<const float *>(g.w), nullptr,
+                      static_cast<float *>(g.y), g.kept, g.N, g.C, g.Nout, g.K, act, s, nullptr, nullptr, nullptr,
+                      nullptr, static_cast<float *>(g.y2));
+}
 
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,

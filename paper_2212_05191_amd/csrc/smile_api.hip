@@ -321,4 +321,116 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
     return from_hip(err);
 }
 
+smile_status smile_backward_workspace_bytes(const smile_layer_desc *desc, size_t *bytes)
+{
+    if (!bytes) return SMILE_INVALID_ARG;
+    smile_status st = smile_validate_desc(desc);
+    if (st != SMILE_OK) return st;
+    *bytes = backward_workspace_layout(*desc).total;
+    return SMILE_OK;
+}
+
+static smile_status check_backward_workspace(const smile_ctx *ctx, const void *workspace, size_t bytes)
+{
+    if (!workspace) return SMILE_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || bytes < backward_workspace_layout(ctx->desc).total)
+        return SMILE_WORKSPACE;
+    return SMILE_OK;
+}
+
+smile_status smile_combine_backward(smile_ctx *ctx, const void *dy, const void *ye, const int32_t *group_idx,
+                                    const int32_t *local_idx, const int32_t *slot, const float *gate,
+                                    void *dye, float *dgate, void *stream)
+{
+    if (!ctx || bad(dy) || bad(ye) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(gate) || bad(dye) ||
+        bad(dgate))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_combine_backward(ctx->desc, dy, ye, group_idx, local_idx, slot, gate, dye, dgate,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, const float *logits_intra,
+                                  const float *bias_inter, const float *bias_intra,
+                                  const int32_t *group_idx, const int32_t *local_idx, const float *dgate,
+                                  const int32_t *group_count, const int32_t *local_count, float dloss,
+                                  float *dlp, float *dlq, void *stream)
+{
+    if (!ctx || bad(logits_inter) || bad(logits_intra) || bad_opt(bias_inter) || bad_opt(bias_intra) ||
+        bad(group_idx) || bad(local_idx) || bad(dgate) || bad(group_count) || bad(local_count) || bad(dlp) || bad(dlq))
+        return SMILE_INVALID_ARG;
+    if (!std::isfinite(dloss)) return SMILE_BAD_SHAPE;
+    return from_hip(launch_route_backward(ctx->desc, logits_inter, logits_intra, bias_inter, bias_intra, group_idx,
+                                          local_idx, dgate, group_count, local_count, dloss, dlp, dlq,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_expert_ffn_backward(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
+                                       const void *w1, const void *w2, const void *dye,
+                                       void *dxe, void *dw1, void *dw2,
+                                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad(w2) || bad(dye) || bad(dxe) || bad(dw1) || bad(dw2))
+        return SMILE_INVALID_ARG;
+    const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
+    if (st != SMILE_OK) return st;
+    return from_hip(launch_expert_ffn_backward(ctx->desc, workspace, xe, kept_count, w1, w2, dye, dxe, dw1, dw2,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_dispatch_backward(smile_ctx *ctx, const void *dxe, const int32_t *group_idx,
+                                     const int32_t *local_idx, const int32_t *slot, const float *dlp,
+                                     const float *dlq, const void *w_inter, const void *w_intra, void *dx,
+                                     void *stream)
+{
+    if (!ctx || bad(dxe) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(dlp) || bad(dlq) || bad(w_inter) ||
+        bad(w_intra) || bad(dx))
+        return SMILE_INVALID_ARG;
+    return from_hip(launch_dispatch_backward(ctx->desc, dxe, group_idx, local_idx, slot, dlp, dlq, w_inter, w_intra,
+                                             dx, static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_gate_weights_backward(smile_ctx *ctx, const void *x, const float *dlp, const float *dlq,
+                                         float *dw_inter, float *dw_intra,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || bad(x) || bad(dlp) || bad(dlq) || bad(dw_inter) || bad(dw_intra)) return SMILE_INVALID_ARG;
+    const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
+    if (st != SMILE_OK) return st;
+    return from_hip(launch_gate_weights_backward(ctx->desc, workspace, x, dlp, dlq, dw_inter, dw_intra,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, float dloss,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || !io) return SMILE_INVALID_ARG;
+    if (bad(io->x) || bad(io->w_inter) || bad(io->w_intra) || bad(io->w1) || bad(io->w2) || bad_opt(io->bias_inter) ||
+        bad_opt(io->bias_intra) || bad(io->logits_inter) || bad(io->logits_intra) || bad(io->group_idx) ||
+        bad(io->local_idx) || bad(io->slot) || bad(io->gate) || bad(io->group_count) || bad(io->local_count) ||
+        bad(io->kept_count) || bad(io->xe) || bad(io->ye) || bad(io->dy) || bad(io->dye) || bad(io->dgate) ||
+        bad(io->dlp) || bad(io->dlq) || bad(io->dxe) || bad(io->dx) || bad(io->dw_inter) || bad(io->dw_intra) ||
+        bad(io->dw1) || bad(io->dw2))
+        return SMILE_INVALID_ARG;
+    if (!std::isfinite(dloss)) return SMILE_BAD_SHAPE;
+    const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
+    if (st != SMILE_OK) return st;
+    const smile_layer_desc &d = ctx->desc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err = launch_combine_backward(d, io->dy, io->ye, io->group_idx, io->local_idx, io->slot, io->gate,
+                                             io->dye, io->dgate, s);
+    if (err == hipSuccess)
+        err = launch_route_backward(d, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
+                                    io->group_idx, io->local_idx, io->dgate, io->group_count, io->local_count, dloss,
+                                    io->dlp, io->dlq, s);
+    if (err == hipSuccess)
+        err = launch_expert_ffn_backward(d, workspace, io->xe, io->kept_count, io->w1, io->w2, io->dye, io->dxe,
+                                         io->dw1, io->dw2, s);
+    if (err == hipSuccess)
+        err = launch_dispatch_backward(d, io->dxe, io->group_idx, io->local_idx, io->slot, io->dlp, io->dlq,
+                                       io->w_inter, io->w_intra, io->dx, s);
+    if (err == hipSuccess)
+        err = launch_gate_weights_backward(d, workspace, io->x, io->dlp, io->dlq, io->dw_inter, io->dw_intra, s);
+    return from_hip(err);
+}
+
 }  // extern "C"

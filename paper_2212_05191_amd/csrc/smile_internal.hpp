@@ -124,12 +124,47 @@ hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws
                                   const void *w2, const void *b2, void *ye, hipStream_t s,
                                   void *y_tokens = nullptr, const float *gate = nullptr);
 
+// One grouped product y[e] = act(x[e] . w[e]^T) over N groups: x[N][C][K], w[N][Nout][K], y[N][C][Nout], rows
+// below kept[e] only (kept == nullptr: all C rows).  act: 0 none, 1 ReLU, 2 GELU.  y2 != nullptr: the product
+// without the activation goes there as well.  bf16 needs K % 64 == 0 and Nout % 8 == 0, fp32 K % 4 == 0.
+struct GroupedGemm {
+    const void *x, *w;
+    void *y, *y2;
+    const int32_t *kept;
+    int N, C, Nout, K, act;
+};
+hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s);
+
 // Last routing step for the fully fused forward pass: pos_in_group / slot as launch_route's finalize
 // kernel, plus the slot -> token map in ws.slot_token, zero output rows for dropped tokens in y, and
 // (loss.out3 != nullptr) the Eq. 4 loss.
 hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, const int32_t *group_idx,
                                const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
                                const LossArgs &loss, hipStream_t s);
+
+// ---- backward pass.  Its workspace is separate from the ctx's and supplied by the caller per call.
+struct BackwardLayout {
+    size_t off_pre, off_h, off_dpre, off_h_t, off_dpre_t, off_dye_t, off_xe_t, off_w_t, off_gw_partial, total;
+    int32_t k_pad;       // capacity rounded up to the GEMM slab depth: contraction length of the weight-gradient GEMMs
+    int32_t gw_blocks;   // token blocks of the router-weight gradient
+};
+BackwardLayout backward_workspace_layout(const smile_layer_desc &d);
+
+hipError_t launch_combine_backward(const smile_layer_desc &d, const void *dy, const void *ye, const int32_t *group_idx,
+                                   const int32_t *local_idx, const int32_t *slot, const float *gate, void *dye,
+                                   float *dgate, hipStream_t s);
+hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_inter, const float *logits_intra,
+                                 const float *bias_inter, const float *bias_intra, const int32_t *group_idx,
+                                 const int32_t *local_idx, const float *dgate, const int32_t *group_count,
+                                 const int32_t *local_count, float dloss, float *dlp, float *dlq, hipStream_t s);
+hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace, const void *xe,
+                                      const int32_t *kept_count, const void *w1, const void *w2, const void *dye,
+                                      void *dxe, void *dw1, void *dw2, hipStream_t s);
+hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
+                                    const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
+                                    const void *w_inter, const void *w_intra, void *dx, hipStream_t s);
+hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspace, const void *x, const float *dlp,
+                                        const float *dlq, float *dw_inter, float *dw_intra, hipStream_t s);
 
 hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
                            const float *p_sum, const float *q_sum, float *out3, hipStream_t s);

@@ -101,6 +101,32 @@ class GpuLayer:
         """The chained entry point without expert buffers: permutations fused into the expert GEMMs."""
         B.smile_layer_forward(self.ctx, self.io_fused)
 
+    # ---- backward pass (buffers and scratch memory are allocated on first use)
+    def prepare_backward(self, dy):
+        """dy: the upstream gradient of y as a host float32 array [T, d] (values representable in the dtype)."""
+        self.dy = to_device(dy, self.cfg.dtype, self.device)
+        if getattr(self, "bwd", None) is None:
+            self.bwd = B.alloc_backward_buffers(self.desc, self.device)
+            nbytes = B.smile_backward_workspace_bytes(self.desc)
+            self.bwd_workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.bwd_io = B.make_backward_io(self.x, self.w_inter, self.w_intra, self.w1, self.w2, self.buf, self.dy,
+                                         self.bwd, self.bias_inter, self.bias_intra)
+
+    def backward_steps(self, dloss=1.0):
+        b, g = self.buf, self.bwd
+        B.smile_combine_backward(self.ctx, self.dy, b.ye, b.group_idx, b.local_idx, b.slot, b.gate, g.dye, g.dgate)
+        B.smile_route_backward(self.ctx, b.logits_inter, b.logits_intra, self.bias_inter, self.bias_intra,
+                               b.group_idx, b.local_idx, g.dgate, b.group_count, b.local_count, dloss, g.dlp, g.dlq)
+        B.smile_expert_ffn_backward(self.ctx, b.xe, b.kept_count, self.w1, self.w2, g.dye, g.dxe, g.dw1, g.dw2,
+                                    self.bwd_workspace)
+        B.smile_dispatch_backward(self.ctx, g.dxe, b.group_idx, b.local_idx, b.slot, g.dlp, g.dlq, self.w_inter,
+                                  self.w_intra, g.dx)
+        B.smile_gate_weights_backward(self.ctx, self.x, g.dlp, g.dlq, g.dw_inter, g.dw_intra, self.bwd_workspace)
+
+    def backward(self, dloss=1.0):
+        """The five backward steps through the single chained entry point."""
+        B.smile_layer_backward(self.ctx, self.bwd_io, dloss, self.bwd_workspace)
+
     def close(self):
         torch.cuda.synchronize()
         self.ctx.close()

@@ -23,7 +23,7 @@ from dataclasses import dataclass
 import numpy as np
 
 # tensor ids used as the second half of the Philox key
-_TID_X, _TID_W_INTER, _TID_W_INTRA, _TID_W1, _TID_W2, _TID_B_INTER, _TID_B_INTRA, _TID_PERM = range(8)
+_TID_X, _TID_W_INTER, _TID_W_INTRA, _TID_W1, _TID_W2, _TID_B_INTER, _TID_B_INTRA, _TID_PERM, _TID_DY = range(9)
 
 
 @dataclass(frozen=True)
@@ -114,6 +114,12 @@ def gen_tokens(cfg: LayerConfig) -> np.ndarray:
     """x[T, d_model] ~ N(0, 1)."""
     x = _rng(cfg.seed, _TID_X).standard_normal((cfg.T, cfg.d_model), dtype=np.float32)
     return quantize(x, cfg.dtype)
+
+
+def gen_output_grad(cfg: LayerConfig) -> np.ndarray:
+    """dy[T, d_model] ~ N(0, 1): the upstream gradient of the layer output for the backward pass."""
+    dy = _rng(cfg.seed, _TID_DY).standard_normal((cfg.T, cfg.d_model), dtype=np.float32)
+    return quantize(dy, cfg.dtype)
 
 
 def gen_router_weights(cfg: LayerConfig) -> tuple[np.ndarray, np.ndarray]:

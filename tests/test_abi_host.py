@@ -159,6 +159,46 @@ def test_entry_points_reject_bad_pointers_before_any_launch():
         assert lib.smile_destroy(h) == B.OK
 
 
+def test_backward_entry_points_reject_bad_arguments_before_any_launch():
+    lib = B.load()
+    d = _desc()
+    h = C.c_void_p(None)
+    fake = 0x7F0000000000
+    assert lib.smile_create_with_workspace(C.byref(d), fake, B.smile_workspace_bytes(d), C.byref(h)) == B.OK
+    p = fake + 4096
+    need = B.smile_backward_workspace_bytes(d)
+    assert need > 0
+    ws = fake + (1 << 30)
+    f1 = C.c_float(1.0)
+    try:
+        assert lib.smile_backward_workspace_bytes(C.byref(d), None) == B.INVALID_ARG
+        assert lib.smile_combine_backward(h, p, p, p, p, p, p, None, p, None) == B.INVALID_ARG
+        assert lib.smile_combine_backward(None, p, p, p, p, p, p, p, p, None) == B.INVALID_ARG
+        assert lib.smile_route_backward(h, p, p, None, None, p, p, p, p, p, f1, p, None, None) == B.INVALID_ARG
+        assert lib.smile_route_backward(h, p, p, None, None, p, p, p, p, p, C.c_float(float("nan")), p, p, None) \
+            == B.BAD_SHAPE
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, None, ws, need, None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, None, need, None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, ws, need - 1, None) == B.WORKSPACE
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, ws + 16, need, None) == B.WORKSPACE
+        assert lib.smile_dispatch_backward(h, p, p, p, p, p, p, p, p + 4, p, None) == B.INVALID_ARG
+        assert lib.smile_gate_weights_backward(h, p, p, p, p, p, ws, need - 1, None) == B.WORKSPACE
+        assert lib.smile_gate_weights_backward(h, p, p, p, None, p, ws, need, None) == B.INVALID_ARG
+        io = B.BackwardIO()
+        for k, _ in B.BackwardIO._fields_:
+            setattr(io, k, p)
+        assert lib.smile_layer_backward(h, None, f1, ws, need, None) == B.INVALID_ARG
+        assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need - 1, None) == B.WORKSPACE
+        io.dw2 = None
+        assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need, None) == B.INVALID_ARG
+        io.dw2 = p
+        io.bias_inter = None        # optional
+        io.dy = p + 2
+        assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need, None) == B.INVALID_ARG
+    finally:
+        assert lib.smile_destroy(h) == B.OK
+
+
 def test_binding_raises_with_status():
     with pytest.raises(B.SmileError) as ei:
         B.smile_workspace_bytes(_desc(T=-5))

@@ -1,0 +1,219 @@
+"""GPU parity of the backward pass: every step through the C-ABI against the CPU oracle's step on the
+same inputs (the oracle step is fed the GPU's outputs of the step before, so each comparison tests one
+step), then the final gradients against the oracle's whole chain."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2212_05191_amd import binding as B
+from paper_2212_05191_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity  # noqa: E402
+from parity import normwise  # noqa: E402
+
+ALPHA, BETA = 0.005, 0.005
+# fp32 sums of up to T products against fp64: far below these; bf16 tensors carry one or two roundings
+TOL_F32_SUM = 2e-5
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.load()
+    return torch
+
+
+def _forward_backward(cfg, chained=False, dloss=1.0, **kw):
+    from paper_2212_05191_amd.runner import GpuLayer
+    _say(f"[case] backward {cfg.name}: T={cfg.T} d={cfg.d_model} F={cfg.d_ff} n={cfg.n_groups} m={cfg.m_local} "
+         f"C={cfg.capacity} Cg={cfg.group_capacity} {cfg.dtype}/{cfg.act} chained={chained}")
+    layer = GpuLayer(cfg, **kw)
+    layer.buf.xe.zero_()
+    layer.buf.ye.zero_()
+    layer.forward()
+    layer.prepare_backward(wl.gen_output_grad(cfg))
+    for k, v in layer.bwd.__dict__.items():
+        v.fill_(-77)
+    layer.bwd.dye.zero_()
+    layer.bwd.dxe.zero_()
+    if chained:
+        layer.backward(dloss)
+    else:
+        layer.backward_steps(dloss)
+    return layer
+
+
+def _fetch_backward(layer):
+    import torch
+    from paper_2212_05191_amd.runner import to_host
+    torch.cuda.synchronize()
+    return {k: to_host(v) for k, v in layer.bwd.__dict__.items()}
+
+
+def _check_steps(cfg, layer, dloss=1.0, experts=None):
+    """experts: None = compare the expert FFN step on every expert, else on the listed ones."""
+    tol = parity.TOL[cfg.dtype]
+    fwd = parity.fetch(layer)
+    out = _fetch_backward(layer)
+    x, wi, wq, bi, bq = parity.host_inputs(cfg)
+    dy = wl.gen_output_grad(cfg)
+    n, m, N, Cap = cfg.n_groups, cfg.m_local, cfg.N, cfg.capacity
+    g, l, slot, kept = fwd["group_idx"], fwd["local_idx"], fwd["slot"], fwd["kept_count"]
+    mask = np.arange(Cap)[None, :] < kept[:, None]
+    info = {}
+
+    # combine backward
+    dye, dgate = oracle.combine_backward(dy, fwd["ye"], g, l, slot, fwd["gate"].astype(np.float64), m, cfg.dtype)
+    info["dye"] = normwise(out["dye"][mask], dye[mask])
+    assert info["dye"] <= tol, "dye"
+    info["dgate"] = normwise(out["dgate"], dgate)
+    assert info["dgate"] <= TOL_F32_SUM, "dgate"
+    assert np.all(out["dgate"][slot < 0] == 0), "a dropped token has no gate gradient"
+
+    # route backward
+    dlp, dlq = oracle.route_backward(fwd["logits_inter"], fwd["logits_intra"], g, l, out["dgate"].astype(np.float64),
+                                     fwd["group_count"], fwd["local_count"], ALPHA, BETA, dloss, bi, bq)
+    info["dlp"], info["dlq"] = normwise(out["dlp"], dlp), normwise(out["dlq"], dlq)
+    assert info["dlp"] <= TOL_F32_SUM and info["dlq"] <= TOL_F32_SUM, "router logit gradients"
+
+    # expert FFN backward
+    es = list(range(N)) if experts is None else list(experts)
+    worst = dict(dxe=0.0, dw1=0.0, dw2=0.0)
+    for e in es:
+        w1, w2 = wl.gen_expert_weights(cfg, e)
+        dxe, dw1, dw2 = oracle.expert_ffn_backward(fwd["xe"][e:e + 1], kept[e:e + 1], w1[None], w2[None],
+                                                   out["dye"][e:e + 1], cfg.act, cfg.dtype)
+        k = int(kept[e])
+        if k:
+            worst["dxe"] = max(worst["dxe"], normwise(out["dxe"][e, :k], dxe[0, :k]))
+            worst["dw1"] = max(worst["dw1"], normwise(out["dw1"][e], dw1[0]))
+            worst["dw2"] = max(worst["dw2"], normwise(out["dw2"][e], dw2[0]))
+        else:
+            assert np.all(out["dw1"][e] == 0) and np.all(out["dw2"][e] == 0), "empty expert: zero weight gradients"
+    info.update(worst)
+    assert worst["dxe"] <= tol and worst["dw1"] <= tol and worst["dw2"] <= tol, f"expert FFN backward {worst}"
+
+    # dispatch backward
+    dx = oracle.dispatch_backward(out["dxe"], g, l, slot, out["dlp"].astype(np.float64), out["dlq"].astype(np.float64),
+                                  wi, wq, cfg.dtype)
+    info["dx"] = normwise(out["dx"], dx)
+    assert info["dx"] <= tol, "dx"
+
+    # router weights backward
+    dwi, dwq = oracle.gate_weights_backward(x, out["dlp"].astype(np.float64), out["dlq"].astype(np.float64))
+    info["dw_inter"], info["dw_intra"] = normwise(out["dw_inter"], dwi), normwise(out["dw_intra"], dwq)
+    assert info["dw_inter"] <= TOL_F32_SUM and info["dw_intra"] <= TOL_F32_SUM, "router weight gradients"
+    return fwd, out, info
+
+
+def _check_end_to_end(cfg, fwd, out, dloss=1.0):
+    """The final gradients against the oracle's own chain (forward from the GPU's logits, so that the routing
+    decisions are the same; everything after that is the oracle's)."""
+    tol = 2 * parity.TOL[cfg.dtype]
+    x, wi, wq, bi, bq = parity.host_inputs(cfg)
+    w1 = np.stack([wl.gen_expert_weights(cfg, e)[0] for e in range(cfg.N)])
+    w2 = np.stack([wl.gen_expert_weights(cfg, e)[1] for e in range(cfg.N)])
+    f = oracle.layer_forward(x, wi, wq, w1, w2, cfg.capacity, cfg.act, cfg.dtype, ALPHA, BETA, bi, bq,
+                             logits=(fwd["logits_inter"], fwd["logits_intra"]), group_capacity=cfg.group_capacity)
+    b = oracle.layer_backward(f, x, wi, wq, w1, w2, wl.gen_output_grad(cfg), cfg.act, cfg.dtype, ALPHA, BETA, dloss,
+                              bi, bq)
+    errs = {k: normwise(out[k], np.asarray(b[k], np.float64)) for k in ("dx", "dw1", "dw2", "dw_inter", "dw_intra")}
+    assert all(v <= tol for v in errs.values()), errs
+    return errs
+
+
+BACKWARD_CASES = [
+    wl.CONFIGS["cfg1"],
+    wl.small_config("bwd_ragged_f32_gelu", 1301, 64, 200, 5, 3, 100, "f32", "gelu", seed=41),
+    wl.small_config("bwd_f32_relu_skew", 900, 72, 136, 3, 2, 120, "f32", "relu", skew=True, seed=42),
+    wl.small_config("bwd_bf16_gelu", 3000, 192, 320, 3, 4, 200, "bf16", "gelu", seed=43),
+    wl.small_config("bwd_bf16_relu_skew", 2500, 128, 448, 4, 8, 90, "bf16", "relu", skew=True, seed=44),
+    wl.small_config("bwd_one_token", 1, 64, 64, 2, 2, 1, "bf16", "gelu", seed=45),
+    wl.small_config("bwd_capacity_one", 300, 64, 128, 2, 3, 1, "bf16", "gelu", seed=46),
+    wl.small_config("bwd_flat", 1500, 128, 128, 1, 12, 100, "bf16", "gelu", seed=47),
+    wl.small_config("bwd_group_cap", 1500, 64, 128, 3, 4, 100, "bf16", "gelu", seed=48, group_capacity=300),
+    wl.small_config("bwd_empty_experts", 40, 64, 64, 4, 4, 8, "f32", "gelu", seed=49),
+]
+
+
+@pytest.mark.parametrize("cfg", BACKWARD_CASES, ids=lambda c: c.name)
+def test_backward_steps_parity(torch_cuda, cfg):
+    layer = _forward_backward(cfg, dloss=1.5)
+    try:
+        fwd, out, info = _check_steps(cfg, layer, dloss=1.5)
+        _say(f"   steps {({k: float(f'{v:.2e}') for k, v in info.items()})}")
+        errs = _check_end_to_end(cfg, fwd, out, dloss=1.5)
+        _say(f"   chain {({k: float(f'{v:.2e}') for k, v in errs.items()})}")
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("cfg", [BACKWARD_CASES[1], BACKWARD_CASES[4]], ids=lambda c: c.name)
+def test_chained_backward_equals_steps_and_repeats(torch_cuda, cfg):
+    a = _forward_backward(cfg)
+    b = _forward_backward(cfg, chained=True)
+    try:
+        oa, ob = _fetch_backward(a), _fetch_backward(b)
+        kept = parity.fetch(a)["kept_count"]
+        mask = np.arange(cfg.capacity)[None, :] < kept[:, None]
+        for k in oa:
+            if k in ("dye", "dxe"):
+                np.testing.assert_array_equal(oa[k][mask], ob[k][mask], err_msg=k)
+            else:
+                np.testing.assert_array_equal(oa[k], ob[k], err_msg=k)
+        b.backward()
+        again = _fetch_backward(b)
+        for k in ob:
+            np.testing.assert_array_equal(ob[k], again[k], err_msg=f"{k} (repeat)")
+    finally:
+        a.close()
+        b.close()
+
+
+def test_backward_large_aux_coefficients(torch_cuda):
+    """Eq. 4 terms large enough to dominate the router gradients (the default 0.005 hides them below the gate term)."""
+    from paper_2212_05191_amd.runner import GpuLayer
+    cfg = wl.small_config("bwd_aux", 700, 64, 64, 4, 3, 80, "f32", "relu", skew=True, seed=50)
+    layer = GpuLayer(cfg, alpha=0.8, beta=0.6)
+    try:
+        layer.forward()
+        dy = np.zeros((cfg.T, cfg.d_model), np.float32)      # no gradient through y: only the loss terms remain
+        layer.prepare_backward(dy)
+        layer.backward(2.0)
+        fwd, out = parity.fetch(layer), _fetch_backward(layer)
+        x, wi, wq, bi, bq = parity.host_inputs(cfg)
+        assert np.all(out["dgate"] == 0)
+        dlp, dlq = oracle.route_backward(fwd["logits_inter"], fwd["logits_intra"], fwd["group_idx"], fwd["local_idx"],
+                                         np.zeros(cfg.T), fwd["group_count"], fwd["local_count"], 0.8, 0.6, 2.0, bi, bq)
+        assert np.abs(dlp).max() > 0
+        assert normwise(out["dlp"], dlp) <= TOL_F32_SUM and normwise(out["dlq"], dlq) <= TOL_F32_SUM
+        dwi, dwq = oracle.gate_weights_backward(x, dlp, dlq)
+        assert normwise(out["dw_inter"], dwi) <= 5e-5 and normwise(out["dw_intra"], dwq) <= 5e-5
+        assert np.all(out["dw1"] == 0) and np.all(out["dw2"] == 0)
+    finally:
+        layer.close()
+
+
+def test_backward_cfg2_sampled(torch_cuda):
+    """The headline configuration at full size: every streaming / router step completely, the expert FFN step on
+    the first, last, fullest and emptiest expert."""
+    cfg = wl.CONFIGS["cfg2"]
+    layer = _forward_backward(cfg, chained=True)
+    try:
+        kept = parity.fetch(layer)["kept_count"]
+        picks = sorted({0, cfg.N - 1, int(np.argmax(kept)), int(np.argmin(kept))})
+        _, _, info = _check_steps(cfg, layer, experts=picks)
+        _say(f"   {({k: float(f'{v:.2e}') for k, v in info.items()})}")
+    finally:
+        layer.close()
