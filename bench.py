@@ -9,7 +9,8 @@ Switch-base-shaped bf16 configuration (T=8192, d=768, F=3072, 2 groups x 8 exper
 Prints ONE JSON line: tokens/s of the whole layer (timed region: K calls of smile_layer_forward),
 the roofline of the dominant kernel (the up-projection + GELU grouped GEMM, timed inside the timed
 region with a HIP event pair that the library attaches to that kernel's launch on its stream),
-per-step times from a second, instrumented pass over the six separate entry points, and the CPU
+per-step times from a second, instrumented pass over the six separate entry points, a third pass
+that times a training step (forward that saves activations, then the backward pass), and the CPU
 oracle timed on the host cores.
 """
 import argparse
@@ -39,6 +40,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload) or t2_48b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip the extra (untimed for `value`) training leg: forward that saves activations + backward")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reads 256 MiB, writes 256 MiB) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE pass of this command has a kernel of known "
@@ -166,6 +169,44 @@ def main():
            for k, v in alg_bytes.items()}
     down_tflops = up_flops / (per_call_us["expert_ffn_down"] * 1e-6) / 1e12
 
+    # ---- third pass (not part of `value`): training step = forward with expert buffers and saved
+    # activations, then the backward pass, each through its single chained entry point
+    train = None
+    if not args.no_backward:
+        layer.enable_saved_activations()
+        layer.prepare_backward(wl.gen_output_grad(cfg))
+        bws = layer.bwd_workspace
+        bw_bytes = bws.numel()
+
+        def fwd_train():
+            st = lib.smile_layer_forward(h, ctypes.byref(layer.io), stream)
+            if st != 0:
+                raise B.SmileError(st, "smile_layer_forward")
+
+        def bwd():
+            st = lib.smile_layer_backward(h, ctypes.byref(layer.bwd_io), ctypes.c_float(1.0), p(bws), bw_bytes, stream)
+            if st != 0:
+                raise B.SmileError(st, "smile_layer_backward")
+
+        def timed(fn, reps):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - c0) / reps
+
+        reps = max(10, min(args.steps, 30))
+        f_s = timed(fwd_train, reps)
+        b_s = timed(bwd, reps)
+        bwd_flops = 8.0 * kept * d * F      # the four gradient GEMMs (dh, dxe, dW1, dW2)
+        train = {"forward_saving_activations_ms": round(f_s * 1e3, 4), "backward_ms": round(b_s * 1e3, 4),
+                 "forward_plus_backward_tokens_per_s": round(T / (f_s + b_s), 1),
+                 "backward_gemm_tflops": round(bwd_flops / b_s / 1e12, 2),
+                 "backward_workspace_MB": round(bw_bytes / 1e6, 1)}
+
     # ---- CPU oracle on the host cores (same workload, one pass)
     cpu = None
     if not args.no_cpu_baseline:
@@ -231,6 +272,7 @@ def main():
                                                          * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "steps_us": {k: round(v, 2) for k, v in per_call_us.items()},
         "hbm": hbm,
+        "training": train,
         "cpu_baseline": cpu,
     }
     layer.close()

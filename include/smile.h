@@ -219,6 +219,10 @@ typedef struct smile_layer_io {
     /* optional: hipEvent_t pair (both or neither) receiving the begin / end timestamps of the
      * up-projection kernel, as in smile_expert_ffn_up_timed; NULL = no timing */
     void *prof_up_start, *prof_up_stop;
+    /* optional (both or neither), for a backward pass that does not recompute them: the hidden
+     * activation h = act(pre) and the pre-activation pre = xe . w1^T + b1, [N,C,F] in the ctx dtype,
+     * rows below kept_count[e] only.  When given, h lives there instead of in the ctx workspace. */
+    void *h_save, *pre_save;
 } smile_layer_io;
 
 /* The whole forward pass in one call: enqueues the six steps above in order on
@@ -271,7 +275,9 @@ smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, con
                                   float *dlp, float *dlq, void *stream);
 
 /* Expert FFN backwards (E_e of Eq. 3, Section 4.1, no bias vectors), rows r < kept_count[e]:
- *   pre = xe[e] . w1[e]^T, h = act(pre)     (recomputed here, both rounded to the ctx dtype)
+ *   pre = xe[e] . w1[e]^T, h = act(pre)     (both rounded to the ctx dtype; taken from h / pre, the
+ *                                            buffers smile_layer_forward saved, or recomputed here
+ *                                            when both are NULL)
  *   dpre = (dye[e] . w2[e]) * act'(pre)
  *   dxe[e] = dpre . w1[e]                                              [N,C,d]
  *   dw2[e][c,f] = sum_r dye[e,r,c] * h[r,f]                            [N,d,F]
@@ -280,6 +286,7 @@ smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, con
  * weight gradients. */
 smile_status smile_expert_ffn_backward(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
                                        const void *w1, const void *w2, const void *dye,
+                                       const void *h, const void *pre,
                                        void *dxe, void *dw1, void *dw2,
                                        void *workspace, size_t workspace_bytes, void *stream);
 
@@ -307,6 +314,7 @@ typedef struct smile_backward_io {
     const float *gate;
     const int32_t *group_count, *local_count, *kept_count;
     const void *xe, *ye;
+    const void *h, *pre;                             /* h_save / pre_save of the forward pass, or both NULL */
     /* upstream gradient of y */
     const void *dy;
     /* intermediates (caller-allocated): dye[N,C,d], dgate[T], dlp[T,n], dlq[T,m], dxe[N,C,d] */

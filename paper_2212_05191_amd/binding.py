@@ -37,14 +37,14 @@ class LayerIO(C.Structure):
         "x", "w_inter", "w_intra", "w1", "b1", "w2", "b2", "bias_inter", "bias_intra",
         "logits_inter", "logits_intra", "group_idx", "local_idx", "pos_in_group", "slot",
         "gate", "p_top", "q_top", "group_count", "local_count", "expert_count", "kept_count",
-        "p_sum", "q_sum", "xe", "ye", "y", "loss3", "prof_up_start", "prof_up_stop")]
+        "p_sum", "q_sum", "xe", "ye", "y", "loss3", "prof_up_start", "prof_up_stop", "h_save", "pre_save")]
 
 
 class BackwardIO(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in (
         "x", "w_inter", "w_intra", "w1", "w2", "bias_inter", "bias_intra",
         "logits_inter", "logits_intra", "group_idx", "local_idx", "slot", "gate",
-        "group_count", "local_count", "kept_count", "xe", "ye", "dy",
+        "group_count", "local_count", "kept_count", "xe", "ye", "h", "pre", "dy",
         "dye", "dgate", "dlp", "dlq", "dxe", "dx", "dw_inter", "dw_intra", "dw1", "dw2")]
 
 
@@ -92,7 +92,7 @@ def load() -> C.CDLL:
     lib.smile_backward_workspace_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
     lib.smile_combine_backward.argtypes = [vp] * 10
     lib.smile_route_backward.argtypes = [vp] * 10 + [C.c_float, vp, vp, vp]
-    lib.smile_expert_ffn_backward.argtypes = [vp] * 10 + [C.c_size_t, vp]
+    lib.smile_expert_ffn_backward.argtypes = [vp] * 12 + [C.c_size_t, vp]
     lib.smile_dispatch_backward.argtypes = [vp] * 11
     lib.smile_gate_weights_backward.argtypes = [vp] * 7 + [C.c_size_t, vp]
     lib.smile_layer_backward.argtypes = [vp, C.POINTER(BackwardIO), C.c_float, vp, C.c_size_t, vp]
@@ -266,9 +266,10 @@ def smile_route_backward(ctx: Ctx, logits_inter, logits_intra, bias_inter, bias_
                                        _stream(stream)), "smile_route_backward")
 
 
-def smile_expert_ffn_backward(ctx: Ctx, xe, kept_count, w1, w2, dye, dxe, dw1, dw2, workspace, stream=None):
+def smile_expert_ffn_backward(ctx: Ctx, xe, kept_count, w1, w2, dye, dxe, dw1, dw2, workspace, h=None, pre=None,
+                              stream=None):
     _check(load().smile_expert_ffn_backward(ctx.handle, _ptr(xe), _ptr(kept_count), _ptr(w1), _ptr(w2), _ptr(dye),
-                                            _ptr(dxe), _ptr(dw1), _ptr(dw2), _ptr(workspace),
+                                            _ptr(h), _ptr(pre), _ptr(dxe), _ptr(dw1), _ptr(dw2), _ptr(workspace),
                                             workspace.numel() * workspace.element_size(), _stream(stream)),
            "smile_expert_ffn_backward")
 
@@ -322,10 +323,10 @@ def alloc_backward_buffers(desc: LayerDesc, device="cuda:0") -> BackwardBuffers:
 
 
 def make_backward_io(x, w_inter, w_intra, w1, w2, fwd: "LayerBuffers", dy, bwd: BackwardBuffers, bias_inter=None,
-                     bias_intra=None) -> BackwardIO:
+                     bias_intra=None, h=None, pre=None) -> BackwardIO:
     io = BackwardIO()
     for k, v in dict(x=x, w_inter=w_inter, w_intra=w_intra, w1=w1, w2=w2, bias_inter=bias_inter,
-                     bias_intra=bias_intra, dy=dy).items():
+                     bias_intra=bias_intra, dy=dy, h=h, pre=pre).items():
         setattr(io, k, _ptr(v))
     for k in ("logits_inter", "logits_intra", "group_idx", "local_idx", "slot", "gate", "group_count", "local_count",
               "kept_count", "xe", "ye"):
@@ -386,4 +387,6 @@ def make_io(x, w_inter, w_intra, w1, w2, buf: LayerBuffers, b1=None, b2=None, bi
         setattr(io, k, _ptr(v))
     for k, v in buf.__dict__.items():
         setattr(io, k, _ptr(v))
+    io.h_save = None
+    io.pre_save = None
     return io

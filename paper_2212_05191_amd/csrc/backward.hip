@@ -5,8 +5,8 @@
 //   combine_backward       dye[row(t)] = gate_t * dy[t],  dgate[t] = <dy[t], ye[row(t)]>     (HBM streaming)
 //   route_backward         softmax Jacobians of the two routers: dgate and the Eq. 4 terms -> dlogits
 //   expert_ffn_backward    five grouped GEMMs on the forward pass's MFMA kernel (all "x . w^T" shaped):
-//                            (pre, h) = xe . W1^T            recomputed, both outputs from one launch
-//                            dh       = dye . (W2^T)^T       then dpre = dh * act'(pre)
+//                            (pre, h) = xe . W1^T            unless saved by the forward pass; one launch
+//                            dpre     = dye . (W2^T)^T  times act'(pre) in the epilogue
 //                            dxe      = dpre . (W1^T)^T
 //                            dW2      = dye^T . (h^T)^T      contraction over the expert's rows
 //                            dW1      = dpre^T . (xe^T)^T
@@ -156,35 +156,6 @@ __global__ __launch_bounds__(kThreads) void route_backward_kernel(
     softmax_backward_row(rq, bq, m, l, mx_q, iz_q, coef_intra, local_count, dg * iz_p, dlq + (size_t)t * m);
 }
 
-// ------------------------------------------------------------------------------------ activation backward
-
-__device__ __forceinline__ float act_grad(float v, int act)
-{
-    if (act == SMILE_ACT_RELU) return v > 0.f ? 1.f : 0.f;
-    // d/dv [v Phi(v)] = Phi(v) + v phi(v)
-    return 0.5f * (1.0f + erff(v * 0.70710678118654752f)) + v * 0.3989422804014327f * expf(-0.5f * v * v);
-}
-
-// dh[e,r,:] *= act'(pre[e,r,:]) in place, rows below kept[e] only.  One thread per 16-byte piece.
-template <bool kBf16>
-__global__ __launch_bounds__(kThreads) void act_backward_kernel(
-    u32x4 *__restrict__ dh, const u32x4 *__restrict__ pre, const int32_t *__restrict__ kept, int C, int ppr, int act,
-    long long pieces)
-{
-    constexpr int E = Piece<kBf16>::kElems;
-    const long long id = (long long)blockIdx.x * kThreads + threadIdx.x;
-    if (id >= pieces) return;
-    const long long row = id / ppr;
-    const int e = (int)(row / C), r = (int)(row - (long long)e * C);
-    if (r >= min(kept[e], C)) return;
-    float a[E], b[E];
-    Piece<kBf16>::unpack(dh[id], a);
-    Piece<kBf16>::unpack(pre[id], b);
-#pragma unroll
-    for (int k = 0; k < E; ++k) a[k] *= act_grad(b[k], act);
-    dh[id] = Piece<kBf16>::pack(a);
-}
-
 // ------------------------------------------------------------------------------------ transpose
 
 // out[e][c][r] = r < rows_e ? in[e][r][c] : 0   for c < cols, r < rows_out;
@@ -285,40 +256,74 @@ __global__ __launch_bounds__(kThreads) void dispatch_backward_kernel(
 
 // ------------------------------------------------------------------------------------ router weights backward
 
-constexpr int kGwTokens = 256;   // tokens per workgroup
+constexpr int kGwTokens = 128;   // tokens per workgroup
 constexpr int kGwCols = 64;      // columns of x per workgroup
+constexpr int kGwChunk = 16;     // logit columns per pass over the token tile
 
 // partial[b][i][k] = sum over the block's tokens of dl[t][i] * x[t][k], i over the n + m logit columns
-// (dlp first, then dlq).  The x tile sits in LDS as fp32; wave w handles logit columns w, w+4, ...,
-// lane = column, so dl[t][i] is uniform over the wave.  Tokens are summed serially: a fixed order.
+// (dlp first, then dlq).  The x tile (fp32) and a chunk of 16 logit-gradient columns sit in LDS; lane =
+// column of x, wave w owns logit columns 4w .. 4w+3 of the chunk, so its four dl values of a token come
+// from one broadcast LDS read.  Tokens are summed serially: a fixed order.
 template <bool kBf16>
 __global__ __launch_bounds__(kThreads) void gate_weights_partial_kernel(
     const void *__restrict__ x, const float *__restrict__ dlp, const float *__restrict__ dlq,
     float *__restrict__ partial, int T, int d, int n, int m)
 {
     __shared__ float xs[kGwTokens][kGwCols + 1];
+    __shared__ __attribute__((aligned(16))) float dls[kGwTokens][kGwChunk];
     const int b = blockIdx.x, k0 = blockIdx.y * kGwCols;
     const int t0 = b * kGwTokens;
     const int cnt = min(kGwTokens, T - t0);
-    for (int id = threadIdx.x; id < kGwTokens * kGwCols; id += kThreads) {
-        const int tt = id / kGwCols, k = id - tt * kGwCols;
-        float v = 0.f;
-        if (tt < cnt && k0 + k < d) {
-            const size_t off = (size_t)(t0 + tt) * d + k0 + k;
-            if constexpr (kBf16) v = __uint_as_float((uint32_t) static_cast<const uint16_t *>(x)[off] << 16);
-            else v = static_cast<const float *>(x)[off];
+    {
+        // x tile: 16-byte pieces, all of a thread's loads issued before the first LDS write (d % 8 == 0)
+        constexpr int E = kBf16 ? 8 : 4, PPT = kGwCols / E, PER = kGwTokens * PPT / kThreads;
+        u32x4 v[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int id = threadIdx.x + q * kThreads, tt = id / PPT, k = (id - tt * PPT) * E;
+            v[q] = u32x4{0u, 0u, 0u, 0u};
+            if (tt < cnt && k0 + k < d)
+                v[q] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(x) +
+                                                        ((size_t)(t0 + tt) * d + k0 + k) * (kBf16 ? 2 : 4));
         }
-        xs[tt][k] = v;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int id = threadIdx.x + q * kThreads, tt = id / PPT, k = (id - tt * PPT) * E;
+            float f[E];
+            Piece<kBf16>::unpack(v[q], f);
+#pragma unroll
+            for (int j = 0; j < E; ++j) xs[tt][k + j] = f[j];
+        }
     }
-    __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cols = n + m;
-    for (int i = wave; i < cols; i += kThreads / 64) {
-        const float *dl = i < n ? dlp + (size_t)t0 * n + i : dlq + (size_t)t0 * m + (i - n);
-        const int stride = i < n ? n : m;
-        float s = 0.f;
-        for (int tt = 0; tt < cnt; ++tt) s = fmaf(dl[(size_t)tt * stride], xs[tt][lane], s);
-        if (k0 + lane < d) partial[((size_t)b * cols + i) * d + k0 + lane] = s;
+    for (int c0 = 0; c0 < cols; c0 += kGwChunk) {
+        __syncthreads();   // x tile ready / previous chunk consumed
+        for (int id = threadIdx.x; id < kGwTokens * kGwChunk; id += kThreads) {
+            const int tt = id / kGwChunk, i = c0 + (id - tt * kGwChunk);
+            float v = 0.f;
+            if (tt < cnt && i < cols)
+                v = i < n ? dlp[(size_t)(t0 + tt) * n + i] : dlq[(size_t)(t0 + tt) * m + (i - n)];
+            dls[tt][id - tt * kGwChunk] = v;
+        }
+        __syncthreads();
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        for (int tt = 0; tt < cnt; ++tt) {
+            const float xv = xs[tt][lane];
+            const float4 g = *reinterpret_cast<const float4 *>(&dls[tt][4 * wave]);
+            s0 = fmaf(g.x, xv, s0);
+            s1 = fmaf(g.y, xv, s1);
+            s2 = fmaf(g.z, xv, s2);
+            s3 = fmaf(g.w, xv, s3);
+        }
+        if (k0 + lane < d) {
+            const float sv[4] = {s0, s1, s2, s3};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = c0 + 4 * wave + j;
+                if (i < cols) partial[((size_t)b * cols + i) * d + k0 + lane] = sv[j];
+            }
+        }
     }
 }
 
@@ -331,6 +336,7 @@ __global__ __launch_bounds__(kThreads) void gate_weights_reduce_kernel(
     const long long total = (long long)(n + m) * d;
     if (id >= total) return;
     float s = 0.f;
+#pragma unroll 8
     for (int b = 0; b < B; ++b) s += partial[(size_t)b * total + id];
     if (id < (long long)n * d) dw_inter[id] = s;
     else dw_intra[id - (long long)n * d] = s;
@@ -415,32 +421,33 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
 
 hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace, const void *xe,
                                       const int32_t *kept_count, const void *w1, const void *w2, const void *dye,
-                                      void *dxe, void *dw1, void *dw2, hipStream_t s)
+                                      const void *h_saved, const void *pre_saved, void *dxe, void *dw1, void *dw2,
+                                      hipStream_t s)
 {
     const BackwardLayout L = backward_workspace_layout(d);
     char *b = static_cast<char *>(workspace);
-    void *pre = b + L.off_pre, *h = b + L.off_h, *dpre = b + L.off_dpre, *h_t = b + L.off_h_t;
+    void *dpre = b + L.off_dpre, *h_t = b + L.off_h_t;
     void *dpre_t = b + L.off_dpre_t, *dye_t = b + L.off_dye_t, *xe_t = b + L.off_xe_t, *w_t = b + L.off_w_t;
     const int N = d.n_groups * d.m_local, C = d.capacity, dm = d.d_model, F = d.d_ff, Kp = L.k_pad;
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
-    const bool bf = d.dtype == SMILE_DTYPE_BF16;
-    const int ppr_f = F * (bf ? 2 : 4) / 16;
     hipError_t err;
 #define SMILE_TRY(call) do { err = (call); if (err != hipSuccess) return err; } while (0)
 
-    // hidden activation and its pre-activation, recomputed
-    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{xe, w1, h, pre, kept_count, N, C, F, dm, act}, s));
-    // dh = dye . W2   (W2 is [d][F]: transposed so that the contraction index is contiguous)
+    // hidden activation and its pre-activation: saved by the forward pass, or recomputed here
+    const void *h = h_saved, *pre = pre_saved;
+    if (!h) {
+        void *h_ws = b + L.off_h, *pre_ws = b + L.off_pre;
+        SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{xe, w1, h_ws, pre_ws, kept_count, N, C, F, dm, act}, s));
+        h = h_ws;
+        pre = pre_ws;
+    }
+    // dpre = (dye . W2) * act'(pre)   (W2 is [d][F]: transposed so that the contraction index is contiguous)
     SMILE_TRY(transpose_pad(d.dtype, w2, w_t, nullptr, N, dm, F, dm, s));                      // W2^T [N][F][d]
-    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dye, w_t, dpre, nullptr, kept_count, N, C, F, dm, 0}, s));
     {
-        const long long pieces = (long long)N * C * ppr_f;
-        const dim3 grid((unsigned)((pieces + kThreads - 1) / kThreads)), block(kThreads);
-        if (bf) hipLaunchKernelGGL(act_backward_kernel<true>, grid, block, 0, s, static_cast<u32x4 *>(dpre),
-                                   static_cast<const u32x4 *>(pre), kept_count, C, ppr_f, d.act, pieces);
-        else hipLaunchKernelGGL(act_backward_kernel<false>, grid, block, 0, s, static_cast<u32x4 *>(dpre),
-                                static_cast<const u32x4 *>(pre), kept_count, C, ppr_f, d.act, pieces);
-        SMILE_TRY(hipGetLastError());
+        GroupedGemm g{dye, w_t, dpre, nullptr, kept_count, N, C, F, dm, 0};
+        g.aux = pre;
+        g.post = act;
+        SMILE_TRY(launch_grouped_gemm_nt(d.dtype, g, s));
     }
     // dW2[c][f] = sum_r dye[r][c] h[r][f]
     SMILE_TRY(transpose_pad(d.dtype, dye, dye_t, kept_count, N, C, dm, Kp, s));                 // [N][d][Kp]

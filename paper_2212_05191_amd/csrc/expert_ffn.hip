@@ -75,6 +75,26 @@ __device__ __forceinline__ float activate(float v)
     } else return v;
 }
 
+// Derivative of the activation at v.  POST 1: ReLU, 2: GELU, d/dv [v Phi(v)] = Phi(v) + v phi(v), with
+// Phi from the same rational erfc approximation as above (|error| < 1.5e-7) and phi sharing its exp.
+template <int POST>
+__device__ __forceinline__ float activate_grad(float v)
+{
+    if constexpr (POST == 1) return v > 0.f ? 1.f : 0.f;
+    else {
+        const float av = fabsf(v);
+        const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, av, 1.0f));
+        float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+        poly = fmaf(poly, t, 0.5f * 1.421413741f);
+        poly = fmaf(poly, t, 0.5f * -0.284496736f);
+        poly = fmaf(poly, t, 0.5f * 0.254829592f);
+        const float ex = __builtin_amdgcn_exp2f(v * v * (-0.5f * 1.4426950408889634f));
+        const float q = poly * t * ex;                      // 1 - Phi(|v|)
+        const float cdf = v >= 0.f ? 1.0f - q : q;
+        return fmaf(v * 0.3989422804014327f, ex, cdf);
+    }
+}
+
 // ------------------------------------------------------------------------------------ bf16 / MFMA
 
 struct GemmArgs {
@@ -91,6 +111,7 @@ struct GemmArgs {
     void *y_tok;            // [T][Nout]
     const float *gate;      // [T]
     void *y2 = nullptr;     // [N][C][Nout]: the same product without the activation (DUAL kernels only)
+    const void *aux = nullptr;   // [N][C][Nout]: POST kernels multiply the output by act'(aux)
 };
 
 // One 16-byte piece (8 bf16) times a gate: fp32 product, rounded to bf16 (nearest even) -- the same
@@ -131,9 +152,12 @@ __device__ __forceinline__ int swz(int row)
 
 // OCC: waves per SIMD the register allocation must leave room for (workgroups per CU when the
 // workgroup has 4 waves).
-// DUAL: the epilogue runs twice, storing act(product) to y and the bare product to y2 (the backward
-// pass recomputes the hidden activation and its pre-activation in one GEMM).
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT, bool DUAL = false>
+// DUAL: the epilogue runs twice, storing act(product) to y and the bare product to y2 (the hidden
+// activation and its pre-activation from one GEMM, for the backward pass).
+// POST (1 ReLU, 2 GELU): the rounded output is multiplied by act'(aux) on its way out (the gradient at the
+// pre-activation, dh * act'(pre)); aux is read with the same row-contiguous 16-byte accesses as the store.
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT, bool DUAL = false,
+          int POST = 0>
 __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
 {
     constexpr int NW = WGM * WGN, NT = NW * 64;
@@ -322,7 +346,22 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
                 const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
                 const int col = ct * BN + piece * 8;
                 if (row < rows && col < Nout) {
-                    const u32x4 v = lds[orow * OSTRIDE + piece];
+                    u32x4 v = lds[orow * OSTRIDE + piece];
+                    if constexpr (POST != 0) {
+                        const u32x4 p = *reinterpret_cast<const u32x4 *>(
+                            static_cast<const __bf16 *>(a.aux) + ((size_t)e * a.C + row) * Nout + col);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const float lo = __uint_as_float(v[k] << 16) * activate_grad<POST>(__uint_as_float(p[k] << 16));
+                            const float hi = __uint_as_float(v[k] & 0xffff0000u) *
+                                             activate_grad<POST>(__uint_as_float(p[k] & 0xffff0000u));
+                            typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+                            bf16x2 pk;
+                            pk[0] = (__bf16)lo;
+                            pk[1] = (__bf16)hi;
+                            v[k] = __builtin_bit_cast(uint32_t, pk);
+                        }
+                    }
                     if (Y) *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = v;
                     if (pass == 0 && y_rows) {   // gate-weighted return to token order (Eq. 3), fused
                         const int tok = y_rows[row];
@@ -357,8 +396,9 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
     return hipGetLastError();
 }
 
-// act(product) and the bare product in one launch (tile 0 only: this is an up-projection shape)
-hipError_t launch_bf16_dual(GemmArgs a, int N, int act, hipStream_t s)
+// The two epilogue variants of the backward pass, on the up-projection tile shape only:
+//   a.y2 given: act(product) and the bare product in one launch;   post != 0: output times act'(a.aux).
+hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t s)
 {
     constexpr int BM = 128, BN = 192;
     a.row_tiles = (a.C + BM - 1) / BM;
@@ -366,8 +406,14 @@ hipError_t launch_bf16_dual(GemmArgs a, int N, int act, hipStream_t s)
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(256);
-    if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
+    if (a.y2) {
+        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
+    } else if (post == 1) {
+        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
+    } else {
+        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
@@ -415,7 +461,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
     const float *__restrict__ x, const float *__restrict__ w, const float *__restrict__ bias,
     float *__restrict__ y, const int32_t *__restrict__ kept, int C, int Nout, int K, int row_tiles, int col_tiles,
     const int32_t *__restrict__ x_rows, const int32_t *__restrict__ y_rows, float *__restrict__ y_tok,
-    const float *__restrict__ gate, float *__restrict__ y2)
+    const float *__restrict__ gate, float *__restrict__ y2, const float *__restrict__ aux, int post)
 {
     constexpr int BT = 64, BK = 16;
     __shared__ float xs[BK][BT + 4];
@@ -472,6 +518,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
             float f = acc[i][j];
             if (bias) f += bias[(size_t)e * Nout + col];
             if (y2) y2[((size_t)e * C + row) * Nout + col] = f;   // the bare product as well
+            if (post) {   // times act'(aux), with the exact erf form in fp32
+                const float p = aux[((size_t)e * C + row) * Nout + col];
+                f *= post == 1 ? (p > 0.f ? 1.f : 0.f)
+                               : 0.5f * (1.0f + erff(p * 0.70710678118654752f)) +
+                                     p * 0.3989422804014327f * expf(-0.5f * p * p);
+            }
             f = activate<ACT>(f);
             if (Y) Y[(size_t)row * Nout + col] = f;
             if (y_rows) y_tok[(size_t)tok * Nout + col] = f * g;
@@ -482,19 +534,19 @@ __global__ __launch_bounds__(256) void grouped_gemm_nt_f32_kernel(
 hipError_t launch_f32(const float *x, const float *w, const float *bias, float *y, const int32_t *kept, int N,
                       int C, int Nout, int K, int act, hipStream_t s, const int32_t *x_rows = nullptr,
                       const int32_t *y_rows = nullptr, float *y_tok = nullptr, const float *gate = nullptr,
-                      float *y2 = nullptr)
+                      float *y2 = nullptr, const float *aux = nullptr, int post = 0)
 {
     const int row_tiles = (C + 63) / 64, col_tiles = (Nout + 63) / 64;
     const dim3 grid(N * row_tiles * col_tiles), block(256);
     if (act == 0)
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<0>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate, y2);
+                           x_rows, y_rows, y_tok, gate, y2, aux, post);
     else if (act == 1)
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<1>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate, y2);
+                           x_rows, y_rows, y_tok, gate, y2, aux, post);
     else
         hipLaunchKernelGGL(grouped_gemm_nt_f32_kernel<2>, grid, block, 0, s, x, w, bias, y, kept, C, Nout, K, row_tiles, col_tiles,
-                           x_rows, y_rows, y_tok, gate, y2);
+                           x_rows, y_rows, y_tok, gate, y2, aux, post);
     return hipGetLastError();
 }
 
@@ -503,27 +555,36 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s)
 {
     const int act = g.act == 0 ? 0 : (g.act == 1 ? 1 : 2);
+    if ((g.y2 && act == 0) || (g.post && (act != 0 || g.y2 || !g.aux))) return hipErrorInvalidValue;
     if (dtype == SMILE_DTYPE_BF16) {
         if (g.K % 64 || g.Nout % 8) return hipErrorInvalidValue;
-        GemmArgs a{g.x, g.w, nullptr, g.y, g.kept, g.C, g.Nout, g.K, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, g.y2};
-        if (g.y2) return launch_bf16_dual(a, g.N, act, s);
+        GemmArgs a{g.x, g.w, g.bias, g.y, g.kept, g.C, g.Nout, g.K, 0, 0, 0, g.x_rows, nullptr, nullptr, nullptr, g.y2, g.aux};
+        if (g.y2 || g.post) return launch_bf16_special(a, g.N, act, g.post, s);
         return launch_bf16(a, g.N, act, pick_tile(g.N, g.C, g.Nout, g.K), s);
     }
     if (g.K % 4) return hipErrorInvalidValue;
-    return launch_f32(static_cast<const float *>(g.x), static_cast<const float *>(g.w), nullptr,
-                      static_cast<float *>(g.y), g.kept, g.N, g.C, g.Nout, g.K, act, s, nullptr, nullptr, nullptr,
-                      nullptr, static_cast<float *>(g.y2));
+    return launch_f32(static_cast<const float *>(g.x), static_cast<const float *>(g.w),
+                      static_cast<const float *>(g.bias), static_cast<float *>(g.y), g.kept, g.N, g.C, g.Nout, g.K, act,
+                      s, g.x_rows, nullptr, nullptr, nullptr, static_cast<float *>(g.y2),
+                      static_cast<const float *>(g.aux), g.post);
 }
 
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
-                                hipEvent_t t0, hipEvent_t t1, const void *x_tokens)
+                                hipEvent_t t0, hipEvent_t t1, const void *x_tokens, void *h_save, void *pre_save)
 {
     const int N = d.n_groups * d.m_local;
     const int act = d.act == SMILE_ACT_RELU ? 1 : 2;
     // x_tokens: read the rows straight from the token matrix through the slot -> token map
     const int32_t *x_rows = x_tokens ? ws.slot_token : nullptr;
     const void *src = x_tokens ? x_tokens : xe;
+    if (h_save) {   // training: the hidden activation and its pre-activation go to the caller's buffers
+        if (t0 && t1) (void)hipEventRecord(t0, s);
+        const hipError_t err = launch_grouped_gemm_nt(
+            d.dtype, GroupedGemm{src, w1, h_save, pre_save, kept_count, N, d.capacity, d.d_ff, d.d_model, act, b1, x_rows}, s);
+        if (t0 && t1) (void)hipEventRecord(t1, s);
+        return err;
+    }
     if (d.dtype == SMILE_DTYPE_BF16) {
         GemmArgs g{src, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0, x_rows, nullptr, nullptr, nullptr};
         return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
@@ -538,16 +599,17 @@ hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, 
 
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
                                   const void *w2, const void *b2, void *ye, hipStream_t s, void *y_tokens,
-                                  const float *gate)
+                                  const float *gate, const void *h_saved)
 {
     const int N = d.n_groups * d.m_local;
+    const void *hidden = h_saved ? h_saved : ws.hidden;
     // y_tokens: also (or, with ye == null, only) return the rows to token order, times the gate
     const int32_t *y_rows = y_tokens ? ws.slot_token : nullptr;
     if (d.dtype == SMILE_DTYPE_BF16) {
-        GemmArgs g{ws.hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0, nullptr, y_rows, y_tokens, gate};
+        GemmArgs g{hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0, nullptr, y_rows, y_tokens, gate};
         return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
     }
-    return launch_f32(static_cast<const float *>(ws.hidden), static_cast<const float *>(w2),
+    return launch_f32(static_cast<const float *>(hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,
                       d.d_model, d.d_ff, 0, s, nullptr, y_rows, static_cast<float *>(y_tokens), gate);
 }

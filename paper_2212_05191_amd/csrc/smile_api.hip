@@ -282,6 +282,8 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         return SMILE_INVALID_ARG;
     if ((io->xe == nullptr) != (io->ye == nullptr)) return SMILE_INVALID_ARG;
     if ((io->prof_up_start == nullptr) != (io->prof_up_stop == nullptr)) return SMILE_INVALID_ARG;
+    if (bad_opt(io->h_save) || bad_opt(io->pre_save) || (io->h_save == nullptr) != (io->pre_save == nullptr))
+        return SMILE_INVALID_ARG;
     // Same kernels as the step-by-step calls with fewer launches.  With expert buffers (xe, ye given):
     // the last routing step and the loss run inside the dispatch kernel.  Without them (both NULL):
     // nothing is materialised -- a per-token kernel finishes the routing, builds the slot -> token map
@@ -304,9 +306,10 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
         if (err == hipSuccess)
             err = launch_expert_ffn_up(d, ctx->ws, nullptr, io->kept_count, io->w1, io->b1, s,
                                        static_cast<hipEvent_t>(io->prof_up_start),
-                                       static_cast<hipEvent_t>(io->prof_up_stop), io->x);
+                                       static_cast<hipEvent_t>(io->prof_up_stop), io->x, io->h_save, io->pre_save);
         if (err == hipSuccess)
-            err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, nullptr, s, io->y, io->gate);
+            err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, nullptr, s, io->y, io->gate,
+                                         io->h_save);
         return from_hip(err);
     }
     if (err == hipSuccess)
@@ -314,8 +317,11 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
                                        io->xe, loss, s);
     if (err == hipSuccess)
         err = launch_expert_ffn_up(d, ctx->ws, io->xe, io->kept_count, io->w1, io->b1, s,
-                                   static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop));
-    if (err == hipSuccess) err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, io->ye, s);
+                                   static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop),
+                                   nullptr, io->h_save, io->pre_save);
+    if (err == hipSuccess)
+        err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, io->ye, s, nullptr, nullptr,
+                                     io->h_save);
     if (err == hipSuccess)
         err = launch_combine(d, io->ye, io->group_idx, io->local_idx, io->slot, io->gate, io->y, s);
     return from_hip(err);
@@ -366,15 +372,17 @@ smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, con
 
 smile_status smile_expert_ffn_backward(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
                                        const void *w1, const void *w2, const void *dye,
+                                       const void *h, const void *pre,
                                        void *dxe, void *dw1, void *dw2,
                                        void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad(w2) || bad(dye) || bad(dxe) || bad(dw1) || bad(dw2))
+    if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad(w2) || bad(dye) || bad(dxe) || bad(dw1) || bad(dw2) ||
+        bad_opt(h) || bad_opt(pre) || (h == nullptr) != (pre == nullptr))
         return SMILE_INVALID_ARG;
     const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
     if (st != SMILE_OK) return st;
-    return from_hip(launch_expert_ffn_backward(ctx->desc, workspace, xe, kept_count, w1, w2, dye, dxe, dw1, dw2,
-                                               static_cast<hipStream_t>(stream)));
+    return from_hip(launch_expert_ffn_backward(ctx->desc, workspace, xe, kept_count, w1, w2, dye, h, pre, dxe, dw1,
+                                               dw2, static_cast<hipStream_t>(stream)));
 }
 
 smile_status smile_dispatch_backward(smile_ctx *ctx, const void *dxe, const int32_t *group_idx,
@@ -409,7 +417,7 @@ smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, f
         bad(io->local_idx) || bad(io->slot) || bad(io->gate) || bad(io->group_count) || bad(io->local_count) ||
         bad(io->kept_count) || bad(io->xe) || bad(io->ye) || bad(io->dy) || bad(io->dye) || bad(io->dgate) ||
         bad(io->dlp) || bad(io->dlq) || bad(io->dxe) || bad(io->dx) || bad(io->dw_inter) || bad(io->dw_intra) ||
-        bad(io->dw1) || bad(io->dw2))
+        bad(io->dw1) || bad(io->dw2) || bad_opt(io->h) || bad_opt(io->pre) || (io->h == nullptr) != (io->pre == nullptr))
         return SMILE_INVALID_ARG;
     if (!std::isfinite(dloss)) return SMILE_BAD_SHAPE;
     const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
@@ -423,8 +431,8 @@ smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, f
                                     io->group_idx, io->local_idx, io->dgate, io->group_count, io->local_count, dloss,
                                     io->dlp, io->dlq, s);
     if (err == hipSuccess)
-        err = launch_expert_ffn_backward(d, workspace, io->xe, io->kept_count, io->w1, io->w2, io->dye, io->dxe,
-                                         io->dw1, io->dw2, s);
+        err = launch_expert_ffn_backward(d, workspace, io->xe, io->kept_count, io->w1, io->w2, io->dye, io->h, io->pre,
+                                         io->dxe, io->dw1, io->dw2, s);
     if (err == hipSuccess)
         err = launch_dispatch_backward(d, io->dxe, io->group_idx, io->local_idx, io->slot, io->dlp, io->dlq,
                                        io->w_inter, io->w_intra, io->dx, s);

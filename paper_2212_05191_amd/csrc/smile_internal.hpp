@@ -116,22 +116,31 @@ hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32
 // up: hidden = act(xe . w1^T + b1) into ws.hidden;  down: ye = hidden . w2^T + b2
 // t0/t1: optional events receiving the begin/end timestamps of the up kernel itself (both or neither)
 // x_tokens != nullptr: gather the input rows from the token matrix x[T,d] through ws.slot_token (xe unused)
+// h_save / pre_save (both or neither): write act(.) there instead of ws.hidden, and the pre-activation too
 hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
-                                hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr, const void *x_tokens = nullptr);
+                                hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr, const void *x_tokens = nullptr,
+                                void *h_save = nullptr, void *pre_save = nullptr);
 // y_tokens != nullptr: also write gate[t] * row to y_tokens[t] for the token t of each row (ye may be null)
 hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
                                   const void *w2, const void *b2, void *ye, hipStream_t s,
-                                  void *y_tokens = nullptr, const float *gate = nullptr);
+                                  void *y_tokens = nullptr, const float *gate = nullptr,
+                                  const void *h_saved = nullptr);
 
 // One grouped product y[e] = act(x[e] . w[e]^T) over N groups: x[N][C][K], w[N][Nout][K], y[N][C][Nout], rows
 // below kept[e] only (kept == nullptr: all C rows).  act: 0 none, 1 ReLU, 2 GELU.  y2 != nullptr: the product
 // without the activation goes there as well.  bf16 needs K % 64 == 0 and Nout % 8 == 0, fp32 K % 4 == 0.
+// bias: [N][Nout] or null.  x_rows != nullptr: input row r of group e is row x_rows[e*C + r] of the matrix x[.][K].
+// post (1 ReLU, 2 GELU; needs act == 0 and aux[N][C][Nout]): the output is multiplied by act'(aux).
 struct GroupedGemm {
     const void *x, *w;
     void *y, *y2;
     const int32_t *kept;
     int N, C, Nout, K, act;
+    const void *bias = nullptr;
+    const int32_t *x_rows = nullptr;
+    const void *aux = nullptr;
+    int post = 0;
 };
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s);
 
@@ -157,9 +166,10 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
                                  const float *bias_inter, const float *bias_intra, const int32_t *group_idx,
                                  const int32_t *local_idx, const float *dgate, const int32_t *group_count,
                                  const int32_t *local_count, float dloss, float *dlp, float *dlq, hipStream_t s);
+// h / pre (both or neither): the hidden activation and pre-activation saved by the forward pass; null: recomputed
 hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace, const void *xe,
                                       const int32_t *kept_count, const void *w1, const void *w2, const void *dye,
-                                      void *dxe, void *dw1, void *dw2, hipStream_t s);
+                                      const void *h, const void *pre, void *dxe, void *dw1, void *dw2, hipStream_t s);
 hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s);

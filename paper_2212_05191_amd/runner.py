@@ -97,6 +97,17 @@ class GpuLayer:
         """All six steps through the single chained entry point (expert buffers materialised)."""
         B.smile_layer_forward(self.ctx, self.io)
 
+    def enable_saved_activations(self):
+        """Training mode of the chained entry points: the forward pass also stores h and the pre-activation
+        ([N,C,F] each) and the backward pass reads them instead of recomputing."""
+        st = torch.bfloat16 if self.cfg.dtype == "bf16" else torch.float32
+        shape = (self.cfg.N, self.cfg.capacity, self.cfg.d_ff)
+        self.h_save = torch.empty(shape, dtype=st, device=self.device)
+        self.pre_save = torch.empty(shape, dtype=st, device=self.device)
+        for io in (self.io, self.io_fused):
+            io.h_save = self.h_save.data_ptr()
+            io.pre_save = self.pre_save.data_ptr()
+
     def forward_fused(self):
         """The chained entry point without expert buffers: permutations fused into the expert GEMMs."""
         B.smile_layer_forward(self.ctx, self.io_fused)
@@ -110,7 +121,8 @@ class GpuLayer:
             nbytes = B.smile_backward_workspace_bytes(self.desc)
             self.bwd_workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self.bwd_io = B.make_backward_io(self.x, self.w_inter, self.w_intra, self.w1, self.w2, self.buf, self.dy,
-                                         self.bwd, self.bias_inter, self.bias_intra)
+                                         self.bwd, self.bias_inter, self.bias_intra,
+                                         getattr(self, "h_save", None), getattr(self, "pre_save", None))
 
     def backward_steps(self, dloss=1.0):
         b, g = self.buf, self.bwd
@@ -118,7 +130,7 @@ class GpuLayer:
         B.smile_route_backward(self.ctx, b.logits_inter, b.logits_intra, self.bias_inter, self.bias_intra,
                                b.group_idx, b.local_idx, g.dgate, b.group_count, b.local_count, dloss, g.dlp, g.dlq)
         B.smile_expert_ffn_backward(self.ctx, b.xe, b.kept_count, self.w1, self.w2, g.dye, g.dxe, g.dw1, g.dw2,
-                                    self.bwd_workspace)
+                                    self.bwd_workspace, getattr(self, "h_save", None), getattr(self, "pre_save", None))
         B.smile_dispatch_backward(self.ctx, g.dxe, b.group_idx, b.local_idx, b.slot, g.dlp, g.dlq, self.w_inter,
                                   self.w_intra, g.dx)
         B.smile_gate_weights_backward(self.ctx, self.x, g.dlp, g.dlq, g.dw_inter, g.dw_intra, self.bwd_workspace)

@@ -154,6 +154,9 @@ def test_entry_points_reject_bad_pointers_before_any_launch():
         io.xe = p
         io.prof_up_stop = None      # timing events come as a pair or not at all
         assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
+        io.prof_up_stop = p
+        io.pre_save = None          # saved activations come as a pair or not at all
+        assert lib.smile_layer_forward(h, C.byref(io), None) == B.INVALID_ARG
         assert lib.smile_expert_ffn_up_timed(h, p, p, p, None, p, None, None) == B.INVALID_ARG
     finally:
         assert lib.smile_destroy(h) == B.OK
@@ -177,10 +180,11 @@ def test_backward_entry_points_reject_bad_arguments_before_any_launch():
         assert lib.smile_route_backward(h, p, p, None, None, p, p, p, p, p, f1, p, None, None) == B.INVALID_ARG
         assert lib.smile_route_backward(h, p, p, None, None, p, p, p, p, p, C.c_float(float("nan")), p, p, None) \
             == B.BAD_SHAPE
-        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, None, ws, need, None) == B.INVALID_ARG
-        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, None, need, None) == B.INVALID_ARG
-        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, ws, need - 1, None) == B.WORKSPACE
-        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, ws + 16, need, None) == B.WORKSPACE
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, None, None, p, p, None, ws, need, None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, None, p, p, p, ws, need, None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, p, p, None, need, None) == B.INVALID_ARG
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, None, None, p, p, p, ws, need - 1, None) == B.WORKSPACE
+        assert lib.smile_expert_ffn_backward(h, p, p, p, p, p, p, p, p, p, p, ws + 16, need, None) == B.WORKSPACE
         assert lib.smile_dispatch_backward(h, p, p, p, p, p, p, p, p + 4, p, None) == B.INVALID_ARG
         assert lib.smile_gate_weights_backward(h, p, p, p, p, p, ws, need - 1, None) == B.WORKSPACE
         assert lib.smile_gate_weights_backward(h, p, p, p, None, p, ws, need, None) == B.INVALID_ARG
@@ -192,6 +196,9 @@ def test_backward_entry_points_reject_bad_arguments_before_any_launch():
         io.dw2 = None
         assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need, None) == B.INVALID_ARG
         io.dw2 = p
+        io.h = None                 # saved activations come as a pair or not at all
+        assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need, None) == B.INVALID_ARG
+        io.pre = None
         io.bias_inter = None        # optional
         io.dy = p + 2
         assert lib.smile_layer_backward(h, C.byref(io), f1, ws, need, None) == B.INVALID_ARG

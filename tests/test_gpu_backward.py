@@ -217,3 +217,58 @@ def test_backward_cfg2_sampled(torch_cuda):
         _say(f"   {({k: float(f'{v:.2e}') for k, v in info.items()})}")
     finally:
         layer.close()
+
+
+@pytest.mark.parametrize("cfg", [BACKWARD_CASES[1], BACKWARD_CASES[3], BACKWARD_CASES[4]], ids=lambda c: c.name)
+def test_saved_activations_equal_recomputation(torch_cuda, cfg):
+    """Forward pass that also stores h and the pre-activation, backward pass that reads them: the forward
+    outputs and every gradient are bit-identical to the path that recomputes them."""
+    torch = torch_cuda
+    from paper_2212_05191_amd.runner import GpuLayer
+    a = _forward_backward(cfg, chained=True)
+    _say(f"[case] saved activations {cfg.name}")
+    b = GpuLayer(cfg)
+    try:
+        b.enable_saved_activations()
+        b.h_save.fill_(-3)
+        b.pre_save.fill_(-3)
+        b.buf.xe.zero_()
+        b.buf.ye.zero_()
+        b.forward()
+        b.prepare_backward(wl.gen_output_grad(cfg))
+        b.backward()
+        fa, fb = parity.fetch(a), parity.fetch(b)
+        kept = fa["kept_count"]
+        mask = np.arange(cfg.capacity)[None, :] < kept[:, None]
+        for k in fa:
+            if k in ("xe", "ye"):
+                np.testing.assert_array_equal(fa[k][mask], fb[k][mask], err_msg=k)
+            else:
+                np.testing.assert_array_equal(fa[k], fb[k], err_msg=k)
+        ga, gb = _fetch_backward(a), _fetch_backward(b)
+        for k in ga:
+            if k in ("dye", "dxe"):
+                np.testing.assert_array_equal(ga[k][mask], gb[k][mask], err_msg=k)
+            else:
+                np.testing.assert_array_equal(ga[k], gb[k], err_msg=k)
+        # rows beyond kept_count of the saved tensors are not written
+        from paper_2212_05191_amd.runner import to_host
+        hs, ps = to_host(b.h_save), to_host(b.pre_save)
+        assert np.all(hs[~mask] == -3) and np.all(ps[~mask] == -3)
+        # h = act(pre) up to the rounding of pre
+        ref = np.maximum(ps[mask], 0) if cfg.act == "relu" else None
+        if ref is not None:
+            np.testing.assert_array_equal(hs[mask], ref)
+        # the fused forward (no expert buffers) saves the same tensors
+        h_first = b.h_save.clone()
+        y_first = b.buf.y.clone()
+        b.h_save.fill_(-3)
+        b.buf.y.fill_(-77)
+        b.forward_fused()
+        torch.cuda.synchronize()
+        assert bool((b.buf.y == y_first).all())
+        m = torch.from_numpy(mask).to(b.h_save.device)
+        assert bool((b.h_save[m] == h_first[m]).all())
+    finally:
+        a.close()
+        b.close()
