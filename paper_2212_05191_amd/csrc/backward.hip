@@ -4,13 +4,12 @@
 //
 //   combine_backward       dye[row(t)] = gate_t * dy[t],  dgate[t] = <dy[t], ye[row(t)]>     (HBM streaming)
 //   route_backward         softmax Jacobians of the two routers: dgate and the Eq. 4 terms -> dlogits
-//   expert_ffn_backward    five grouped GEMMs on the forward pass's MFMA kernel (all "x . w^T" shaped):
-//                            (pre, h) = xe . W1^T            unless saved by the forward pass; one launch
-//                            dpre     = dye . (W2^T)^T  times act'(pre) in the epilogue
-//                            dxe      = dpre . (W1^T)^T
-//                            dW2      = dye^T . (h^T)^T      contraction over the expert's rows
-//                            dW1      = dpre^T . (xe^T)^T
-//                          the transposed operands are made by a tiled transpose kernel (zero-padded
+//   expert_ffn_backward    (pre, h) = xe . W1^T   unless saved by the forward pass (one launch of the forward kernel)
+//                          dpre = (dye . W2) * act'(pre),  dxe = dpre . W1,
+//                          dW2 = dye^T . h,  dW1 = dpre^T . xe   (contraction over the expert's rows)
+//                          bf16: four launches of the MFMA kernel that reads operands whose contraction index is
+//                          the slow one (transposing LDS reads), nothing transposed in memory;
+//                          fp32: the forward kernel on operands transposed by a tiled transpose kernel (zero-padded
 //                          along the row axis, so experts with fewer than C rows contribute exact zeros)
 //   dispatch_backward      dx[t] = dxe[row(t)] + dlp[t,:] . W_p + dlq[t,:] . W_q
 //   gate_weights_backward  dW_p = dlp^T . x, dW_q = dlq^T . x: per-block partial sums, then a fixed-order
@@ -308,6 +307,7 @@ __global__ __launch_bounds__(kThreads) void gate_weights_partial_kernel(
         }
         __syncthreads();
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll 8
         for (int tt = 0; tt < cnt; ++tt) {
             const float xv = xs[tt][lane];
             const float4 g = *reinterpret_cast<const float4 *>(&dls[tt][4 * wave]);
@@ -372,11 +372,13 @@ BackwardLayout backward_workspace_layout(const smile_layer_desc &d)
     L.off_pre = off;     off = align_up(off + N * C * F * esz, 256);
     L.off_h = off;       off = align_up(off + N * C * F * esz, 256);
     L.off_dpre = off;    off = align_up(off + N * C * F * esz, 256);
-    L.off_h_t = off;     off = align_up(off + N * F * (size_t)L.k_pad * esz, 256);
-    L.off_dpre_t = off;  off = align_up(off + N * F * (size_t)L.k_pad * esz, 256);
-    L.off_dye_t = off;   off = align_up(off + N * dm * (size_t)L.k_pad * esz, 256);
-    L.off_xe_t = off;    off = align_up(off + N * dm * (size_t)L.k_pad * esz, 256);
-    L.off_w_t = off;     off = align_up(off + N * dm * F * esz, 256);
+    // transposed copies of the operands: the fp32 path only (the bf16 kernel reads them in place)
+    const size_t tr = d.dtype == SMILE_DTYPE_BF16 ? 0 : 1;
+    L.off_h_t = off;     off = align_up(off + tr * N * F * (size_t)L.k_pad * esz, 256);
+    L.off_dpre_t = off;  off = align_up(off + tr * N * F * (size_t)L.k_pad * esz, 256);
+    L.off_dye_t = off;   off = align_up(off + tr * N * dm * (size_t)L.k_pad * esz, 256);
+    L.off_xe_t = off;    off = align_up(off + tr * N * dm * (size_t)L.k_pad * esz, 256);
+    L.off_w_t = off;     off = align_up(off + tr * N * dm * F * esz, 256);
     L.off_gw_partial = off;
     off = align_up(off + (size_t)L.gw_blocks * (size_t)(d.n_groups + d.m_local) * dm * sizeof(float), 256);
     L.total = off;
@@ -441,6 +443,24 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
         h = h_ws;
         pre = pre_ws;
     }
+    if (d.dtype == SMILE_DTYPE_BF16) {
+        // MFMA kernel that reads operands with the contraction index as the slow index: no transposed copies
+        const long long cd = (long long)C * dm, cf = (long long)C * F, df = (long long)dm * F;
+        // dpre[r,f] = (sum_c dye[r,c] W2[c,f]) * act'(pre[r,f])
+        SMILE_TRY(launch_grouped_gemm_t_bf16(
+            TransposedGemm{dye, w2, dpre, pre, kept_count, nullptr, N, C, F, dm, dm, F, cd, df, cf, false, true, act}, s));
+        // dW2[c,f] = sum_r dye[r,c] h[r,f]
+        SMILE_TRY(launch_grouped_gemm_t_bf16(
+            TransposedGemm{dye, h, dw2, nullptr, nullptr, kept_count, N, dm, F, C, dm, F, cd, cf, df, true, true, 0}, s));
+        // dxe[r,k] = sum_f dpre[r,f] W1[f,k]
+        SMILE_TRY(launch_grouped_gemm_t_bf16(
+            TransposedGemm{dpre, w1, dxe, nullptr, kept_count, nullptr, N, C, dm, F, F, dm, cf, df, cd, false, true, 0}, s));
+        // dW1[f,k] = sum_r dpre[r,f] xe[r,k]
+        SMILE_TRY(launch_grouped_gemm_t_bf16(
+            TransposedGemm{dpre, xe, dw1, nullptr, nullptr, kept_count, N, F, dm, C, F, dm, cf, cd, df, true, true, 0}, s));
+        return hipSuccess;
+    }
+    // fp32: the same four products on the x . w^T kernel, with explicitly transposed operands
     // dpre = (dye . W2) * act'(pre)   (W2 is [d][F]: transposed so that the contraction index is contiguous)
     SMILE_TRY(transpose_pad(d.dtype, w2, w_t, nullptr, N, dm, F, dm, s));                      // W2^T [N][F][d]
     {

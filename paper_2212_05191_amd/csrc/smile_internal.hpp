@@ -144,6 +144,23 @@ struct GroupedGemm {
 };
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s);
 
+// One grouped bf16 product y[e][i][j] = sum_k X(i,k) W(j,k) whose operands may have the contraction index as
+// their slow index (x_transposed: x[e] is [K][Mrows]; w_transposed: w[e] is [K][Nout]); a normal x is
+// [Mrows][K].  ldx / ldw: leading dimensions, sx / sw / sy: per-group strides, all in elements.
+// rows_valid[e] (or Mrows) output rows are computed; k_valid[e] (or K) terms are summed (transposed operands
+// only: a normal operand needs K % 64 == 0 and full K).  post (1 ReLU, 2 GELU): times act'(aux), aux shaped as y.
+struct TransposedGemm {
+    const void *x, *w;
+    void *y;
+    const void *aux;
+    const int32_t *rows_valid, *k_valid;
+    int N, Mrows, Nout, K, ldx, ldw;
+    long long sx, sw, sy;
+    bool x_transposed, w_transposed;
+    int post;
+};
+hipError_t launch_grouped_gemm_t_bf16(const TransposedGemm &g, hipStream_t s);
+
 // Last routing step for the fully fused forward pass: pos_in_group / slot as launch_route's finalize
 // kernel, plus the slot -> token map in ws.slot_token, zero output rows for dropped tokens in y, and
 // (loss.out3 != nullptr) the Eq. 4 loss.
