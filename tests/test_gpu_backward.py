@@ -144,6 +144,9 @@ BACKWARD_CASES = [
     wl.small_config("bwd_flat", 1500, 128, 128, 1, 12, 100, "bf16", "gelu", seed=47),
     wl.small_config("bwd_group_cap", 1500, 64, 128, 3, 4, 100, "bf16", "gelu", seed=48, group_capacity=300),
     wl.small_config("bwd_empty_experts", 40, 64, 64, 4, 4, 8, "f32", "gelu", seed=49),
+    wl.small_config("bwd_bf16_empty_experts", 40, 64, 128, 4, 4, 8, "bf16", "gelu", seed=51),
+    # contraction lengths of the weight-gradient GEMMs from 0 to several 64-row slabs with ragged ends
+    wl.small_config("bwd_bf16_long_ragged", 4099, 128, 256, 2, 4, 700, "bf16", "gelu", skew=True, seed=52),
 ]
 
 
@@ -205,11 +208,12 @@ def test_backward_large_aux_coefficients(torch_cuda):
         layer.close()
 
 
-def test_backward_cfg2_sampled(torch_cuda):
-    """The headline configuration at full size: every streaming / router step completely, the expert FFN step on
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_backward_full_size_sampled(torch_cuda, name):
+    """Benchmark configurations at full size: every streaming / router step completely, the expert FFN step on
     the first, last, fullest and emptiest expert."""
-    cfg = wl.CONFIGS["cfg2"]
-    layer = _forward_backward(cfg, chained=True)
+    cfg = wl.CONFIGS[name]
+    layer = _forward_backward(cfg, chained=True, workers=16)
     try:
         kept = parity.fetch(layer)["kept_count"]
         picks = sorted({0, cfg.N - 1, int(np.argmax(kept)), int(np.argmin(kept))})
