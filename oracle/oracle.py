@@ -20,7 +20,7 @@ _LIB = os.path.join(_HERE, "libsmile_oracle.so")
 _lib = None
 
 _ACT = {"relu": 0, "gelu": 1}
-_DTYPE = {"f32": 0, "bf16": 1}
+_DTYPE = {"f32": 0, "bf16": 1, "f16": 2}
 
 
 def build(force: bool = True) -> str:

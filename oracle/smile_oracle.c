@@ -18,9 +18,10 @@
  *     per group (the paper's GPUs per node), N = n*m experts, flat expert id
  *     e = i*m + j for expert j of group i (Section 3.2.1, E_{i,j}).
  *   - C = capacity = rows of each expert's buffer.
- *   - dtype 0: storage is fp32; dtype 1: storage is bfloat16, so values that
- *     the layer stores (hidden activation h, expert output, layer output) are
- *     rounded to bfloat16 (nearest, ties to even) where they would be stored.
+ *   - dtype 0: storage is fp32; dtype 1: storage is bfloat16, dtype 2: IEEE
+ *     half precision (the precision the paper trains in, Section 4.1), so values
+ *     that the layer stores (hidden activation h, expert output, layer output)
+ *     are rounded to that type (nearest, ties to even) where they would be stored.
  *
  * Readings of points the paper leaves open (all listed in the design notes):
  *   - Eq. 1 is read as a softmax, as the sentence introducing it says.
@@ -81,9 +82,26 @@ static double round_bf16(double v)
     return q * ulp;
 }
 
+/* nearest binary16 value (IEEE half: 11 significant bits, exponents -14..15, subnormals below 2^-14,
+ * ties to even, overflow to infinity) */
+static double round_f16(double v)
+{
+    if (v == 0.0 || !isfinite(v)) return v;
+    int ex;
+    (void)frexp(v, &ex);
+    int e = ex - 1;               /* |v| in [2^e, 2^(e+1)) */
+    if (e < -14) e = -14;
+    double ulp = ldexp(1.0, e - 10);
+    double q = nearbyint(v / ulp) * ulp;
+    if (fabs(q) > 65504.0) return v > 0 ? INFINITY : -INFINITY;
+    return q;
+}
+
 static double store_round(double v, int dtype)
 {
-    return dtype == 1 ? round_bf16(v) : (double)(float)v;
+    if (dtype == 1) return round_bf16(v);
+    if (dtype == 2) return round_f16(v);
+    return (double)(float)v;
 }
 
 /* Router logits r(x) = W_r x (Section 2, before Eq. 1), once for the inter

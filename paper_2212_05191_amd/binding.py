@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsmile.so")
 _lib = None
 
-DTYPE = {"f32": 0, "bf16": 1}
+DTYPE = {"f32": 0, "bf16": 1, "f16": 2}
 ACT = {"relu": 0, "gelu": 1}
 
 OK, INVALID_ARG, BAD_SHAPE, UNSUPPORTED, WORKSPACE, HIP_ERROR = range(6)
@@ -245,6 +245,13 @@ def smile_layer_forward(ctx: Ctx, io: LayerIO, stream=None):
     _check(load().smile_layer_forward(ctx.handle, C.byref(io), _stream(stream)), "smile_layer_forward")
 
 
+def torch_dtype(dtype):
+    """torch storage type of a desc.dtype code or name."""
+    import torch
+    code = DTYPE[dtype] if isinstance(dtype, str) else int(dtype)
+    return {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}[code]
+
+
 # ------------------------------------------------------------------ backward pass
 
 def smile_backward_workspace_bytes(desc: LayerDesc) -> int:
@@ -312,7 +319,7 @@ def alloc_backward_buffers(desc: LayerDesc, device="cuda:0") -> BackwardBuffers:
     import torch
     T, d, F, n, m, Cap = desc.T, desc.d_model, desc.d_ff, desc.n_groups, desc.m_local, desc.capacity
     N = n * m
-    st = torch.bfloat16 if desc.dtype == DTYPE["bf16"] else torch.float32
+    st = torch_dtype(desc.dtype)
     f32 = torch.float32
 
     def e(shape, dt):
@@ -366,7 +373,7 @@ def alloc_buffers(desc: LayerDesc, device="cuda:0") -> LayerBuffers:
     import torch
     T, d, n, m, Cap = desc.T, desc.d_model, desc.n_groups, desc.m_local, desc.capacity
     N = n * m
-    st = torch.bfloat16 if desc.dtype == DTYPE["bf16"] else torch.float32
+    st = torch_dtype(desc.dtype)
     f32, i32 = torch.float32, torch.int32
 
     def e(shape, dt):

@@ -16,6 +16,8 @@ def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
     if dtype == "bf16":
         bits = wl.f32_to_bf16_bits(a).view(np.int16)
         return torch.from_numpy(bits).to(device).view(torch.bfloat16).reshape(a.shape)
+    if dtype == "f16":
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).astype(np.float16)).to(device)
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
 
 
@@ -23,6 +25,8 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     """Device tensor -> host numpy (bf16 widened to float32, exactly)."""
     if t.dtype == torch.bfloat16:
         return wl.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).reshape(t.shape)
+    if t.dtype == torch.float16:
+        return t.cpu().numpy().astype(np.float32)
     return t.cpu().numpy()
 
 
@@ -38,7 +42,7 @@ class GpuLayer:
         self.x = to_device(wl.gen_tokens(cfg), cfg.dtype, device)
         wi, wq = wl.gen_router_weights(cfg)
         self.w_inter, self.w_intra = to_device(wi, cfg.dtype, device), to_device(wq, cfg.dtype, device)
-        st = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        st = B.torch_dtype(cfg.dtype)
         self.w1 = torch.empty((cfg.N, cfg.d_ff, cfg.d_model), dtype=st, device=device)
         self.w2 = torch.empty((cfg.N, cfg.d_model, cfg.d_ff), dtype=st, device=device)
         with ThreadPoolExecutor(max_workers=workers) as pool:
@@ -100,7 +104,7 @@ class GpuLayer:
     def enable_saved_activations(self):
         """Training mode of the chained entry points: the forward pass also stores h and the pre-activation
         ([N,C,F] each) and the backward pass reads them instead of recomputing."""
-        st = torch.bfloat16 if self.cfg.dtype == "bf16" else torch.float32
+        st = B.torch_dtype(self.cfg.dtype)
         shape = (self.cfg.N, self.cfg.capacity, self.cfg.d_ff)
         self.h_save = torch.empty(shape, dtype=st, device=self.device)
         self.pre_save = torch.empty(shape, dtype=st, device=self.device)

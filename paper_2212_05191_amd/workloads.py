@@ -41,7 +41,7 @@ class LayerConfig:
     m_local: int      # m: second-level (intra) routing fan-out
     capacity_factor: float
     capacity: int     # rows per expert buffer
-    dtype: str        # "f32" or "bf16": storage type of x, weights, buffers, y
+    dtype: str        # "f32", "bf16" or "f16": storage type of x, weights, buffers, y
     act: str          # "relu" or "gelu"
     skew: bool = False  # add routing biases (Zipf inter-group, Gaussian per-expert)
     seed: int = 0
@@ -102,6 +102,8 @@ def quantize(a: np.ndarray, dtype: str) -> np.ndarray:
         return a
     if dtype == "bf16":
         return bf16_bits_to_f32(f32_to_bf16_bits(a))
+    if dtype == "f16":
+        return a.astype(np.float16).astype(np.float32)
     raise ValueError(f"unknown dtype {dtype!r}")
 
 

@@ -9,7 +9,8 @@ logits would legitimately flip the routing):
         (dispatch is a copy: bit-exact);
   (iv)  oracle run fully independently: tokens routed differently must all be near-ties.
 
-Tolerances (norm-wise, max|a-b| / max|b| per tensor): 1e-5 in fp32, 2e-2 in bf16.
+Tolerances (norm-wise, max|a-b| / max|b| per tensor): 1e-5 in fp32, 2e-2 in bf16, 4e-3 in fp16 (8 units of
+its 2^-11 rounding error: the same few roundings as bf16 with 8 times finer steps).
 """
 from __future__ import annotations
 
@@ -19,7 +20,7 @@ import oracle
 from paper_2212_05191_amd import workloads as wl
 from paper_2212_05191_amd.runner import GpuLayer, to_host
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 4e-3}
 NEAR_TIE = 1e-4
 
 

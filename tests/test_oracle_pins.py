@@ -396,6 +396,39 @@ def test_bf16_storage_rounding_matches_library(rng):
     np.testing.assert_array_equal(wl.quantize(vals, "bf16"), want)
 
 
+def test_f16_storage_rounding_matches_library(rng):
+    # the same pure store in half precision against numpy's and torch's float16 conversions: normal numbers,
+    # ties (1 + 2^-11 rounds to even), the subnormal range below 2^-14, and overflow beyond 65504
+    vals = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-8, 5, 4000),
+                           [1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -10, 0.0, -0.0, 2.0 ** -15,
+                            2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, 6.1e-5, 65504.0, 65519.9, 65520.0, -70000.0]]
+                          ).astype(np.float32)
+    ye = vals.reshape(1, -1, 1)
+    Tn = ye.shape[1]
+    y = oracle.combine(ye, np.zeros(Tn, np.int32), np.zeros(Tn, np.int32), np.arange(Tn, dtype=np.int32),
+                       np.ones(Tn), 1, "f16")
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).astype(np.float32)
+    np.testing.assert_array_equal(y[:, 0], want)
+    np.testing.assert_array_equal(torch.from_numpy(vals).to(torch.float16).float().numpy(), want)
+    finite = np.isfinite(want)
+    np.testing.assert_array_equal(wl.quantize(vals[finite], "f16"), want[finite])
+    assert np.isinf(want).sum() == 2 and (want[finite] != vals[finite]).any()
+
+
+def test_f16_hidden_rounding_is_applied_between_the_two_matmuls():
+    # h = 1 + 2^-12 is not a half-precision number; it must round to 1.0 before the second matmul
+    x = np.array([[[1.0 + 2.0 ** -12]]], np.float32)
+    one = np.array([[[1.0]]], np.float32)
+    y16 = oracle.expert_ffn(x, [1], one, one, "relu", "f16")
+    y32 = oracle.expert_ffn(x, [1], one, one, "relu", "f32")
+    assert y16[0, 0, 0] == 1.0 and y32[0, 0, 0] == np.float32(1.0 + 2.0 ** -12)
+    # but 1 + 2^-9 (which bf16 drops) survives in half precision
+    x = np.array([[[1.0 + 2.0 ** -9]]], np.float32)
+    assert oracle.expert_ffn(x, [1], one, one, "relu", "f16")[0, 0, 0] == np.float32(1.0 + 2.0 ** -9)
+    assert oracle.expert_ffn(x, [1], one, one, "relu", "bf16")[0, 0, 0] == 1.0
+
+
 def test_bf16_hidden_rounding_is_applied_between_the_two_matmuls():
     # h = 1 + 2^-9 is not a bf16 number; it must round to 1.0 before the second matmul
     x = np.array([[[1.0 + 2.0 ** -9]]], np.float32)
