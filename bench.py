@@ -23,7 +23,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM bytes per launch of the dominant kernel (up-projection GEMM) from the two rocprofv3 --pmc passes
@@ -38,7 +38,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload) or t2_48b")
+    ap.add_argument("--workload", default="cfg2", help="cfg1..cfg5 (cfg2 is the headline workload), t2_48b, cfg4_flat or cfg2_f16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip the extra (untimed for `value`) training leg: forward that saves activations + backward")
@@ -139,7 +139,7 @@ def main():
     kept = int(b.kept_count.sum().item())
     dropped = cfg.T - kept
     ecnt = b.expert_count.cpu().numpy()
-    s = 2 if cfg.dtype == "bf16" else 4
+    s = 4 if cfg.dtype == "f32" else 2
     d, F, T, N = cfg.d_model, cfg.d_ff, cfg.T, cfg.N
     up_flops = 2.0 * kept * d * F
     achieved_tflops = up_flops / (dom_ms * 1e-3) / 1e12

@@ -24,10 +24,11 @@
  *   - Notation: T tokens, d = d_model, F = d_ff, n = n_groups, m = m_local,
  *     N = n*m, flat expert id e = group*m + local, C = capacity (rows of each
  *     expert's buffer).  dtype is the storage type of x, router and expert
- *     weights, the expert buffers and y: 0 = fp32, 1 = bfloat16.  Logits,
- *     probabilities, gates and the loss are always fp32.
- *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for bf16:
- *     d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096;
+ *     weights, the expert buffers and y: 0 = fp32, 1 = bfloat16, 2 = IEEE half.
+ *     Logits, probabilities, gates and the loss are always fp32; products of
+ *     16-bit values accumulate in fp32 on the matrix cores.
+ *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for the 16-bit
+ *     types: d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096;
  *     N*C*max(d,F) < 2^40 elements; N*C and T below 2^31 (T <= 2^30 with a
  *     group capacity).  n = 1 (or m = 1)
  *     gives the flat one-level top-1 router of Section 2 (Eq. 1-2, k = 1).
@@ -52,7 +53,7 @@ typedef enum smile_status {
     SMILE_HIP_ERROR = 5      /* a HIP runtime call failed (allocation, launch) */
 } smile_status;
 
-enum { SMILE_DTYPE_F32 = 0, SMILE_DTYPE_BF16 = 1 };
+enum { SMILE_DTYPE_F32 = 0, SMILE_DTYPE_BF16 = 1, SMILE_DTYPE_F16 = 2 };   /* F16: IEEE half, the paper's training precision (Section 4.1) */
 enum { SMILE_ACT_RELU = 0, SMILE_ACT_GELU = 1 };   /* GELU is the exact erf form (Section 4.1) */
 
 /* Static description of one layer; copied by smile_create. */

@@ -14,6 +14,8 @@
 //   dispatch_backward      dx[t] = dxe[row(t)] + dlp[t,:] . W_p + dlq[t,:] . W_q
 //   gate_weights_backward  dW_p = dlp^T . x, dW_q = dlq^T . x: per-block partial sums, then a fixed-order
 //                          reduction over the blocks (bit-reproducible, no atomics)
+#include <type_traits>
+
 #include "smile_internal.hpp"
 
 namespace smile {
@@ -23,27 +25,17 @@ namespace {
 constexpr int kThreads = 256;
 
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
-__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    bf16x2 pk;
-    pk[0] = (__bf16)lo;   // round to nearest even
-    pk[1] = (__bf16)hi;
-    return __builtin_bit_cast(uint32_t, pk);
-}
-
-// A 16-byte piece as 4 (fp32) or 8 (bf16) floats and back.
-template <bool kBf16>
+// A 16-byte piece as 4 (fp32) or 8 (16-bit types) floats and back.  DT: SMILE_DTYPE_*.
+template <int DT>
 struct Piece {
-    static constexpr int kElems = kBf16 ? 8 : 4;
+    static constexpr int kElems = DT == SMILE_DTYPE_F32 ? 4 : 8;
+    using H = Half<std::conditional_t<DT == SMILE_DTYPE_F16, _Float16, __bf16>>;
     __device__ static __forceinline__ void unpack(u32x4 v, float (&f)[kElems])
     {
-        if constexpr (kBf16) {
+        if constexpr (DT != SMILE_DTYPE_F32) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) { f[2 * k] = bf16_lo(v[k]); f[2 * k + 1] = bf16_hi(v[k]); }
+            for (int k = 0; k < 4; ++k) { f[2 * k] = H::lo(v[k]); f[2 * k + 1] = H::hi(v[k]); }
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) f[k] = __uint_as_float(v[k]);
@@ -52,9 +44,9 @@ struct Piece {
     __device__ static __forceinline__ u32x4 pack(const float (&f)[kElems])
     {
         u32x4 r;
-        if constexpr (kBf16) {
+        if constexpr (DT != SMILE_DTYPE_F32) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) r[k] = pack_bf16(f[2 * k], f[2 * k + 1]);
+            for (int k = 0; k < 4; ++k) r[k] = H::pack(f[2 * k], f[2 * k + 1]);
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) r[k] = __float_as_uint(f[k]);
@@ -66,13 +58,13 @@ struct Piece {
 // ------------------------------------------------------------------------------------ combine backward
 
 // LPR consecutive lanes own one token row (as in the forward dispatch / combine kernels).
-template <bool kBf16, int LPR>
+template <int DT, int LPR>
 __global__ __launch_bounds__(kThreads) void combine_backward_kernel(
     const u32x4 *__restrict__ dy, const u32x4 *__restrict__ ye, const int32_t *__restrict__ group_idx,
     const int32_t *__restrict__ local_idx, const int32_t *__restrict__ slot, const float *__restrict__ gate,
     u32x4 *__restrict__ dye, float *__restrict__ dgate, int T, int ppr, int m, int C)
 {
-    constexpr int E = Piece<kBf16>::kElems;
+    constexpr int E = Piece<DT>::kElems;
     const int t = blockIdx.x * (kThreads / LPR) + threadIdx.x / LPR, sub = threadIdx.x % LPR;
     // every lane of a row group takes the same branch, and a group never straddles a wave
     if (t >= T) return;
@@ -88,14 +80,14 @@ __global__ __launch_bounds__(kThreads) void combine_backward_kernel(
     float dot = 0.f;
     for (int c = sub; c < ppr; c += LPR) {
         float a[E], b[E], o[E];
-        Piece<kBf16>::unpack(src[c], a);
-        Piece<kBf16>::unpack(act[c], b);
+        Piece<DT>::unpack(src[c], a);
+        Piece<DT>::unpack(act[c], b);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             dot = fmaf(a[k], b[k], dot);
             o[k] = a[k] * gt;
         }
-        dst[c] = Piece<kBf16>::pack(o);
+        dst[c] = Piece<DT>::pack(o);
     }
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
@@ -210,21 +202,21 @@ hipError_t launch_transpose(const void *in, void *out, const int32_t *kept, int 
 hipError_t transpose_pad(int dtype, const void *in, void *out, const int32_t *kept, int N, int R, int cols,
                          int rows_out, hipStream_t s)
 {
-    if (dtype == SMILE_DTYPE_BF16) return launch_transpose<uint16_t, 8>(in, out, kept, N, R, cols, rows_out, s);
+    if (is_half(dtype)) return launch_transpose<uint16_t, 8>(in, out, kept, N, R, cols, rows_out, s);
     return launch_transpose<float, 4>(in, out, kept, N, R, cols, rows_out, s);
 }
 
 // ------------------------------------------------------------------------------------ dispatch backward
 
 // dx[t] = dxe[row(t)] (kept tokens) + sum_i dlp[t,i] W_p[i] + sum_j dlq[t,j] W_q[j], one rounding.
-template <bool kBf16, int LPR>
+template <int DT, int LPR>
 __global__ __launch_bounds__(kThreads) void dispatch_backward_kernel(
     const u32x4 *__restrict__ dxe, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ slot, const float *__restrict__ dlp, const float *__restrict__ dlq,
     const u32x4 *__restrict__ w_inter, const u32x4 *__restrict__ w_intra, u32x4 *__restrict__ dx,
     int T, int ppr, int n, int m, int C)
 {
-    constexpr int E = Piece<kBf16>::kElems;
+    constexpr int E = Piece<DT>::kElems;
     const int t = blockIdx.x * (kThreads / LPR) + threadIdx.x / LPR, sub = threadIdx.x % LPR;
     if (t >= T) return;
     const int sl = slot[t];
@@ -232,24 +224,24 @@ __global__ __launch_bounds__(kThreads) void dispatch_backward_kernel(
     const float *lp = dlp + (size_t)t * n, *lq = dlq + (size_t)t * m;
     for (int c = sub; c < ppr; c += LPR) {
         float acc[E], w[E];
-        if (src) Piece<kBf16>::unpack(src[c], acc);
+        if (src) Piece<DT>::unpack(src[c], acc);
         else {
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[k] = 0.f;
         }
         for (int i = 0; i < n; ++i) {
             const float g = lp[i];
-            Piece<kBf16>::unpack(w_inter[(size_t)i * ppr + c], w);
+            Piece<DT>::unpack(w_inter[(size_t)i * ppr + c], w);
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[k] = fmaf(g, w[k], acc[k]);
         }
         for (int j = 0; j < m; ++j) {
             const float g = lq[j];
-            Piece<kBf16>::unpack(w_intra[(size_t)j * ppr + c], w);
+            Piece<DT>::unpack(w_intra[(size_t)j * ppr + c], w);
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[k] = fmaf(g, w[k], acc[k]);
         }
-        dx[(size_t)t * ppr + c] = Piece<kBf16>::pack(acc);
+        dx[(size_t)t * ppr + c] = Piece<DT>::pack(acc);
     }
 }
 
@@ -263,7 +255,7 @@ constexpr int kGwChunk = 16;     // logit columns per pass over the token tile
 // (dlp first, then dlq).  The x tile (fp32) and a chunk of 16 logit-gradient columns sit in LDS; lane =
 // column of x, wave w owns logit columns 4w .. 4w+3 of the chunk, so its four dl values of a token come
 // from one broadcast LDS read.  Tokens are summed serially: a fixed order.
-template <bool kBf16>
+template <int DT>
 __global__ __launch_bounds__(kThreads) void gate_weights_partial_kernel(
     const void *__restrict__ x, const float *__restrict__ dlp, const float *__restrict__ dlq,
     float *__restrict__ partial, int T, int d, int n, int m)
@@ -275,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void gate_weights_partial_kernel(
     const int cnt = min(kGwTokens, T - t0);
     {
         // x tile: 16-byte pieces, all of a thread's loads issued before the first LDS write (d % 8 == 0)
-        constexpr int E = kBf16 ? 8 : 4, PPT = kGwCols / E, PER = kGwTokens * PPT / kThreads;
+        constexpr int E = Piece<DT>::kElems, PPT = kGwCols / E, PER = kGwTokens * PPT / kThreads;
         u32x4 v[PER];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
@@ -283,13 +275,13 @@ __global__ __launch_bounds__(kThreads) void gate_weights_partial_kernel(
             v[q] = u32x4{0u, 0u, 0u, 0u};
             if (tt < cnt && k0 + k < d)
                 v[q] = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(x) +
-                                                        ((size_t)(t0 + tt) * d + k0 + k) * (kBf16 ? 2 : 4));
+                                                        ((size_t)(t0 + tt) * d + k0 + k) * (16 / E));
         }
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const int id = threadIdx.x + q * kThreads, tt = id / PPT, k = (id - tt * PPT) * E;
             float f[E];
-            Piece<kBf16>::unpack(v[q], f);
+            Piece<DT>::unpack(v[q], f);
 #pragma unroll
             for (int j = 0; j < E; ++j) xs[tt][k + j] = f[j];
         }
@@ -360,10 +352,18 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
     default: { constexpr int L = 32; CALL; } break; \
     }
 
+// CALL with the compile-time constant DT set to the runtime storage type
+#define SMILE_DTYPE_SWITCH(dtype, CALL)                                             \
+    switch (dtype) {                                                                \
+    case SMILE_DTYPE_BF16: { constexpr int DT = SMILE_DTYPE_BF16; CALL; } break;    \
+    case SMILE_DTYPE_F16: { constexpr int DT = SMILE_DTYPE_F16; CALL; } break;      \
+    default: { constexpr int DT = SMILE_DTYPE_F32; CALL; } break;                   \
+    }
+
 BackwardLayout backward_workspace_layout(const smile_layer_desc &d)
 {
     BackwardLayout L{};
-    const size_t esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
+    const size_t esz = elem_size(d.dtype);
     const size_t N = (size_t)d.n_groups * d.m_local, C = (size_t)d.capacity;
     const size_t dm = (size_t)d.d_model, F = (size_t)d.d_ff;
     L.k_pad = (int32_t)((d.capacity + 63) / 64 * 64);
@@ -373,7 +373,7 @@ BackwardLayout backward_workspace_layout(const smile_layer_desc &d)
     L.off_h = off;       off = align_up(off + N * C * F * esz, 256);
     L.off_dpre = off;    off = align_up(off + N * C * F * esz, 256);
     // transposed copies of the operands: the fp32 path only (the bf16 kernel reads them in place)
-    const size_t tr = d.dtype == SMILE_DTYPE_BF16 ? 0 : 1;
+    const size_t tr = is_half(d.dtype) ? 0 : 1;
     L.off_h_t = off;     off = align_up(off + tr * N * F * (size_t)L.k_pad * esz, 256);
     L.off_dpre_t = off;  off = align_up(off + tr * N * F * (size_t)L.k_pad * esz, 256);
     L.off_dye_t = off;   off = align_up(off + tr * N * dm * (size_t)L.k_pad * esz, 256);
@@ -389,21 +389,13 @@ hipError_t launch_combine_backward(const smile_layer_desc &d, const void *dy, co
                                    const int32_t *local_idx, const int32_t *slot, const float *gate, void *dye,
                                    float *dgate, hipStream_t s)
 {
-    const bool bf = d.dtype == SMILE_DTYPE_BF16;
-    const int ppr = d.d_model * (bf ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    if (bf) {
-        SMILE_BWD_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_backward_kernel<true, L>), grid, block, 0, s,
-                                                     static_cast<const u32x4 *>(dy), static_cast<const u32x4 *>(ye),
-                                                     group_idx, local_idx, slot, gate, static_cast<u32x4 *>(dye), dgate,
-                                                     d.T, ppr, d.m_local, d.capacity));
-    } else {
-        SMILE_BWD_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_backward_kernel<false, L>), grid, block, 0, s,
-                                                     static_cast<const u32x4 *>(dy), static_cast<const u32x4 *>(ye),
-                                                     group_idx, local_idx, slot, gate, static_cast<u32x4 *>(dye), dgate,
-                                                     d.T, ppr, d.m_local, d.capacity));
-    }
+    SMILE_DTYPE_SWITCH(d.dtype, SMILE_BWD_LPR_SWITCH(
+        lpr, hipLaunchKernelGGL((combine_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dy),
+                                static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
+                                static_cast<u32x4 *>(dye), dgate, d.T, ppr, d.m_local, d.capacity)));
     return hipGetLastError();
 }
 
@@ -443,21 +435,21 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
         h = h_ws;
         pre = pre_ws;
     }
-    if (d.dtype == SMILE_DTYPE_BF16) {
+    if (is_half(d.dtype)) {
         // MFMA kernel that reads operands with the contraction index as the slow index: no transposed copies
         const long long cd = (long long)C * dm, cf = (long long)C * F, df = (long long)dm * F;
         // dpre[r,f] = (sum_c dye[r,c] W2[c,f]) * act'(pre[r,f])
-        SMILE_TRY(launch_grouped_gemm_t_bf16(
-            TransposedGemm{dye, w2, dpre, pre, kept_count, nullptr, N, C, F, dm, dm, F, cd, df, cf, false, true, act}, s));
+        SMILE_TRY(launch_grouped_gemm_t(
+            d.dtype, TransposedGemm{dye, w2, dpre, pre, kept_count, nullptr, N, C, F, dm, dm, F, cd, df, cf, false, true, act}, s));
         // dW2[c,f] = sum_r dye[r,c] h[r,f]
-        SMILE_TRY(launch_grouped_gemm_t_bf16(
-            TransposedGemm{dye, h, dw2, nullptr, nullptr, kept_count, N, dm, F, C, dm, F, cd, cf, df, true, true, 0}, s));
+        SMILE_TRY(launch_grouped_gemm_t(
+            d.dtype, TransposedGemm{dye, h, dw2, nullptr, nullptr, kept_count, N, dm, F, C, dm, F, cd, cf, df, true, true, 0}, s));
         // dxe[r,k] = sum_f dpre[r,f] W1[f,k]
-        SMILE_TRY(launch_grouped_gemm_t_bf16(
-            TransposedGemm{dpre, w1, dxe, nullptr, kept_count, nullptr, N, C, dm, F, F, dm, cf, df, cd, false, true, 0}, s));
+        SMILE_TRY(launch_grouped_gemm_t(
+            d.dtype, TransposedGemm{dpre, w1, dxe, nullptr, kept_count, nullptr, N, C, dm, F, F, dm, cf, df, cd, false, true, 0}, s));
         // dW1[f,k] = sum_r dpre[r,f] xe[r,k]
-        SMILE_TRY(launch_grouped_gemm_t_bf16(
-            TransposedGemm{dpre, xe, dw1, nullptr, nullptr, kept_count, N, F, dm, C, F, dm, cf, cd, df, true, true, 0}, s));
+        SMILE_TRY(launch_grouped_gemm_t(
+            d.dtype, TransposedGemm{dpre, xe, dw1, nullptr, nullptr, kept_count, N, F, dm, C, F, dm, cf, cd, df, true, true, 0}, s));
         return hipSuccess;
     }
     // fp32: the same four products on the x . w^T kernel, with explicitly transposed operands
@@ -488,23 +480,14 @@ hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, 
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s)
 {
-    const bool bf = d.dtype == SMILE_DTYPE_BF16;
-    const int ppr = d.d_model * (bf ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    if (bf) {
-        SMILE_BWD_LPR_SWITCH(lpr, hipLaunchKernelGGL((dispatch_backward_kernel<true, L>), grid, block, 0, s,
-                                                     static_cast<const u32x4 *>(dxe), group_idx, local_idx, slot, dlp,
-                                                     dlq, static_cast<const u32x4 *>(w_inter),
-                                                     static_cast<const u32x4 *>(w_intra), static_cast<u32x4 *>(dx), d.T,
-                                                     ppr, d.n_groups, d.m_local, d.capacity));
-    } else {
-        SMILE_BWD_LPR_SWITCH(lpr, hipLaunchKernelGGL((dispatch_backward_kernel<false, L>), grid, block, 0, s,
-                                                     static_cast<const u32x4 *>(dxe), group_idx, local_idx, slot, dlp,
-                                                     dlq, static_cast<const u32x4 *>(w_inter),
-                                                     static_cast<const u32x4 *>(w_intra), static_cast<u32x4 *>(dx), d.T,
-                                                     ppr, d.n_groups, d.m_local, d.capacity));
-    }
+    SMILE_DTYPE_SWITCH(d.dtype, SMILE_BWD_LPR_SWITCH(
+        lpr, hipLaunchKernelGGL((dispatch_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dxe),
+                                group_idx, local_idx, slot, dlp, dlq, static_cast<const u32x4 *>(w_inter),
+                                static_cast<const u32x4 *>(w_intra), static_cast<u32x4 *>(dx), d.T, ppr, d.n_groups,
+                                d.m_local, d.capacity)));
     return hipGetLastError();
 }
 
@@ -514,12 +497,8 @@ hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspa
     const BackwardLayout L = backward_workspace_layout(d);
     float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_gw_partial);
     const dim3 grid(L.gw_blocks, (d.d_model + kGwCols - 1) / kGwCols), block(kThreads);
-    if (d.dtype == SMILE_DTYPE_BF16)
-        hipLaunchKernelGGL(gate_weights_partial_kernel<true>, grid, block, 0, s, x, dlp, dlq, partial, d.T, d.d_model,
-                           d.n_groups, d.m_local);
-    else
-        hipLaunchKernelGGL(gate_weights_partial_kernel<false>, grid, block, 0, s, x, dlp, dlq, partial, d.T, d.d_model,
-                           d.n_groups, d.m_local);
+    SMILE_DTYPE_SWITCH(d.dtype, hipLaunchKernelGGL(gate_weights_partial_kernel<DT>, grid, block, 0, s, x, dlp, dlq,
+                                                   partial, d.T, d.d_model, d.n_groups, d.m_local));
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long long total = (long long)(d.n_groups + d.m_local) * d.d_model;

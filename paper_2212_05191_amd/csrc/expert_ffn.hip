@@ -45,8 +45,6 @@ namespace smile {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
@@ -114,21 +112,14 @@ struct GemmArgs {
     const void *aux = nullptr;   // [N][C][Nout]: POST kernels multiply the output by act'(aux)
 };
 
-// One 16-byte piece (8 bf16) times a gate: fp32 product, rounded to bf16 (nearest even) -- the same
-// arithmetic as the stand-alone combine kernel.
-__device__ __forceinline__ u32x4 scale_bf16x8(u32x4 v, float g)
+// One 16-byte piece (8 elements) times a gate: fp32 product, rounded to the storage type (nearest even) --
+// the same arithmetic as the stand-alone combine kernel.
+template <typename E>
+__device__ __forceinline__ u32x4 scale_x8(u32x4 v, float g)
 {
     u32x4 r;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const float lo = __uint_as_float(v[k] << 16) * g;
-        const float hi = __uint_as_float(v[k] & 0xffff0000u) * g;
-        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-        bf16x2 pk;
-        pk[0] = (__bf16)lo;
-        pk[1] = (__bf16)hi;
-        r[k] = __builtin_bit_cast(uint32_t, pk);
-    }
+    for (int k = 0; k < 4; ++k) r[k] = Half<E>::pack(Half<E>::lo(v[k]) * g, Half<E>::hi(v[k]) * g);
     return r;
 }
 
@@ -156,10 +147,13 @@ __device__ __forceinline__ int swz(int row)
 // activation and its pre-activation from one GEMM, for the backward pass).
 // POST (1 ReLU, 2 GELU): the rounded output is multiplied by act'(aux) on its way out (the gradient at the
 // pre-activation, dh * act'(pre)); aux is read with the same row-contiguous 16-byte accesses as the store.
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT, bool DUAL = false,
-          int POST = 0>
+// E: the 16-bit storage type (__bf16 or _Float16).
+template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT,
+          bool DUAL = false, int POST = 0>
 __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
 {
+    typedef typename Half<E>::vec8 bf16x8;                                  // one MFMA operand: 8 elements
+    typedef __attribute__((__vector_size__(4 * sizeof(E)))) E bf16x4;       // 4 rounded outputs
     constexpr int NW = WGM * WGN, NT = NW * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
@@ -190,8 +184,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     if (rt * BM >= rows) return;
 
     const int K = a.K, Nout = a.Nout;
-    const __bf16 *X = static_cast<const __bf16 *>(a.x) + (a.x_rows ? (size_t)0 : (size_t)e * a.C * K);
-    const __bf16 *W = static_cast<const __bf16 *>(a.w) + (size_t)e * Nout * K;
+    const E *X = static_cast<const E *>(a.x) + (a.x_rows ? (size_t)0 : (size_t)e * a.C * K);
+    const E *W = static_cast<const E *>(a.w) + (size_t)e * Nout * K;
     const int32_t *x_rows = a.x_rows ? a.x_rows + (size_t)e * a.C : nullptr;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -200,7 +194,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
 
     // ---- this lane's source address in each of the wave's load instructions
     const int lr = lane / PPR, lp = lane % PPR;
-    const __bf16 *src[GPW];
+    const E *src[GPW];
 #pragma unroll
     for (int i = 0; i < GPW; ++i) {
         const int row = (wave + i * NW) * RPI + lr;            // row of the stage
@@ -291,7 +285,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = Half<E>::mfma_32x32x16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j]);
             // order inside the k-step: MFMA, LDS read, MFMA, LDS read, ... then MFMA + global loads
             constexpr int NM = TM * TN, ND = TM + TN;
 #pragma unroll
@@ -313,13 +307,13 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
     // activation + rounding, 8-byte writes into a [OROWS][BN] staging tile, then row-contiguous
     // 16-byte global stores by the whole workgroup.
     const int32_t *y_rows = a.y_rows ? a.y_rows + (size_t)e * a.C : nullptr;
-    const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (size_t)e * Nout : nullptr;
+    const E *bias = a.bias ? static_cast<const E *>(a.bias) + (size_t)e * Nout : nullptr;
     u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
     constexpr int OPR = BN / 8;   // 16-byte pieces per output row
 #pragma unroll
     for (int pass = 0; pass < (DUAL ? 2 : 1); ++pass) {
         void *dst = pass == 0 ? a.y : a.y2;
-        __bf16 *Y = dst ? static_cast<__bf16 *>(dst) + (size_t)e * a.C * Nout : nullptr;
+        E *Y = dst ? static_cast<E *>(dst) + (size_t)e * a.C * Nout : nullptr;
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
@@ -334,7 +328,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
                     for (int v = 0; v < 4; ++v) {
                         float f = acc[i][j][4 * q + v];
                         if (bias) f += (float)bias[min(ct * BN + lcol + v, Nout - 1)];
-                        out[v] = (__bf16)(pass == 0 ? activate<ACT>(f) : f);
+                        out[v] = (E)(pass == 0 ? activate<ACT>(f) : f);
                     }
                     stg[((wm * 32 + frow) * OSTRIDE) * 2 + (lcol >> 2)] = __builtin_bit_cast(u32x2, out);
                 }
@@ -349,24 +343,17 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kerne
                     u32x4 v = lds[orow * OSTRIDE + piece];
                     if constexpr (POST != 0) {
                         const u32x4 p = *reinterpret_cast<const u32x4 *>(
-                            static_cast<const __bf16 *>(a.aux) + ((size_t)e * a.C + row) * Nout + col);
+                            static_cast<const E *>(a.aux) + ((size_t)e * a.C + row) * Nout + col);
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const float lo = __uint_as_float(v[k] << 16) * activate_grad<POST>(__uint_as_float(p[k] << 16));
-                            const float hi = __uint_as_float(v[k] & 0xffff0000u) *
-                                             activate_grad<POST>(__uint_as_float(p[k] & 0xffff0000u));
-                            typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-                            bf16x2 pk;
-                            pk[0] = (__bf16)lo;
-                            pk[1] = (__bf16)hi;
-                            v[k] = __builtin_bit_cast(uint32_t, pk);
-                        }
+                        for (int k = 0; k < 4; ++k)
+                            v[k] = Half<E>::pack(Half<E>::lo(v[k]) * activate_grad<POST>(Half<E>::lo(p[k])),
+                                                 Half<E>::hi(v[k]) * activate_grad<POST>(Half<E>::hi(p[k])));
                     }
                     if (Y) *reinterpret_cast<u32x4 *>(Y + (size_t)row * Nout + col) = v;
                     if (pass == 0 && y_rows) {   // gate-weighted return to token order (Eq. 3), fused
                         const int tok = y_rows[row];
-                        *reinterpret_cast<u32x4 *>(static_cast<__bf16 *>(a.y_tok) + (size_t)tok * Nout + col) =
-                            scale_bf16x8(v, a.gate[tok]);
+                        *reinterpret_cast<u32x4 *>(static_cast<E *>(a.y_tok) + (size_t)tok * Nout + col) =
+                            scale_x8<E>(v, a.gate[tok]);
                     }
                 }
             }
@@ -382,7 +369,7 @@ void launch_timed(Kernel k, dim3 grid, dim3 block, hipStream_t s, hipEvent_t t0,
     else hipLaunchKernelGGL(k, grid, block, 0, s, a);
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
+template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
 hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     a.row_tiles = (a.C + BM - 1) / BM;
@@ -390,14 +377,15 @@ hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(WGM * WGN * 64);
-    if (act == 0) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
-    else if (act == 1) launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
-    else launch_timed(grouped_gemm_nt_bf16_kernel<BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
+    if (act == 0) launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
+    else if (act == 1) launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
+    else launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
     return hipGetLastError();
 }
 
 // The two epilogue variants of the backward pass, on the up-projection tile shape only:
 //   a.y2 given: act(product) and the bare product in one launch;   post != 0: output times act'(a.aux).
+template <typename E>
 hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t s)
 {
     constexpr int BM = 128, BN = 192;
@@ -407,12 +395,12 @@ hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(256);
     if (a.y2) {
-        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
+        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
     } else if (post == 1) {
-        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }
@@ -426,17 +414,18 @@ hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t
 //     wins -- four stages of 128x192 when the grid has at most one tile per CU, else three stages
 //     of 128x256 (fewer weight bytes through L2 per flop).
 // Larger tiles (256x128 .. 256x256) move fewer bytes L2 -> LDS per flop but were never faster here.
+template <typename E>
 hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
                        hipEvent_t t1 = nullptr)
 {
     switch (tile) {
-    case 0: return launch_bf16_tile<128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 1: return launch_bf16_tile<128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
-    case 2: return launch_bf16_tile<128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
-    case 3: return launch_bf16_tile<256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
-    case 4: return launch_bf16_tile<128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
-    case 5: return launch_bf16_tile<64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 6: return launch_bf16_tile<256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 0: return launch_bf16_tile<E, 128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 1: return launch_bf16_tile<E, 128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
+    case 2: return launch_bf16_tile<E, 128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
+    case 3: return launch_bf16_tile<E, 256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
+    case 4: return launch_bf16_tile<E, 128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 5: return launch_bf16_tile<E, 64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 6: return launch_bf16_tile<E, 256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
     default: return hipErrorInvalidValue;
     }
 }
@@ -550,17 +539,32 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
     return hipGetLastError();
 }
 
+
+// dtype dispatch of the two MFMA launchers
+hipError_t launch_half(int dtype, const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
+                       hipEvent_t t1 = nullptr)
+{
+    if (dtype == SMILE_DTYPE_BF16) return launch_bf16<__bf16>(a, N, act, tile, s, t0, t1);
+    return launch_bf16<_Float16>(a, N, act, tile, s, t0, t1);
+}
+
+hipError_t launch_half_special(int dtype, const GemmArgs &a, int N, int act, int post, hipStream_t s)
+{
+    if (dtype == SMILE_DTYPE_BF16) return launch_bf16_special<__bf16>(a, N, act, post, s);
+    return launch_bf16_special<_Float16>(a, N, act, post, s);
+}
+
 }  // namespace
 
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s)
 {
     const int act = g.act == 0 ? 0 : (g.act == 1 ? 1 : 2);
     if ((g.y2 && act == 0) || (g.post && (act != 0 || g.y2 || !g.aux))) return hipErrorInvalidValue;
-    if (dtype == SMILE_DTYPE_BF16) {
+    if (is_half(dtype)) {
         if (g.K % 64 || g.Nout % 8) return hipErrorInvalidValue;
         GemmArgs a{g.x, g.w, g.bias, g.y, g.kept, g.C, g.Nout, g.K, 0, 0, 0, g.x_rows, nullptr, nullptr, nullptr, g.y2, g.aux};
-        if (g.y2 || g.post) return launch_bf16_special(a, g.N, act, g.post, s);
-        return launch_bf16(a, g.N, act, pick_tile(g.N, g.C, g.Nout, g.K), s);
+        if (g.y2 || g.post) return launch_half_special(dtype, a, g.N, act, g.post, s);
+        return launch_half(dtype, a, g.N, act, pick_tile(g.N, g.C, g.Nout, g.K), s);
     }
     if (g.K % 4) return hipErrorInvalidValue;
     return launch_f32(static_cast<const float *>(g.x), static_cast<const float *>(g.w),
@@ -585,9 +589,9 @@ hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, 
         if (t0 && t1) (void)hipEventRecord(t1, s);
         return err;
     }
-    if (d.dtype == SMILE_DTYPE_BF16) {
+    if (is_half(d.dtype)) {
         GemmArgs g{src, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0, x_rows, nullptr, nullptr, nullptr};
-        return launch_bf16(g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
+        return launch_half(d.dtype, g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
     }
     if (t0 && t1) (void)hipEventRecord(t0, s);
     const hipError_t err = launch_f32(static_cast<const float *>(src), static_cast<const float *>(w1),
@@ -605,9 +609,9 @@ hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws
     const void *hidden = h_saved ? h_saved : ws.hidden;
     // y_tokens: also (or, with ye == null, only) return the rows to token order, times the gate
     const int32_t *y_rows = y_tokens ? ws.slot_token : nullptr;
-    if (d.dtype == SMILE_DTYPE_BF16) {
+    if (is_half(d.dtype)) {
         GemmArgs g{hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0, nullptr, y_rows, y_tokens, gate};
-        return launch_bf16(g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
+        return launch_half(d.dtype, g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
     }
     return launch_f32(static_cast<const float *>(hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,

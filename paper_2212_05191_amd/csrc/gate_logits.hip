@@ -19,29 +19,30 @@ namespace smile {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kRows = 16;      // token rows per workgroup
 constexpr int kWaves = 4;      // K-split factor
 
 // CT = number of 16-column tiles covering the n+m logits columns; RT = 16-row tiles per workgroup.
-template <int CT, int RT>
-__global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
-    const __bf16 *__restrict__ x, const __bf16 *__restrict__ w_inter, const __bf16 *__restrict__ w_intra,
+// E: __bf16 or _Float16.
+template <typename E, int CT, int RT>
+__global__ __launch_bounds__(64 * kWaves) void gate_logits_half_kernel(
+    const E *__restrict__ x, const E *__restrict__ w_inter, const E *__restrict__ w_intra,
     float *__restrict__ logits_inter, float *__restrict__ logits_intra, int T, int d, int n, int m, int col0)
 {
+    typedef typename Half<E>::vec8 bf16x8;   // 8 elements: one MFMA operand
     __shared__ f32x4 red[kWaves - 1][RT][CT][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, kg = lane >> 4;
     const int row0 = blockIdx.x * kRows * RT;
-    const __bf16 *xrow[RT];
+    const E *xrow[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) xrow[rt] = x + (size_t)min(row0 + rt * kRows + r, T - 1) * d;
 
     // the weight row this lane feeds as the B operand of column tile ct (null: padding column)
-    const __bf16 *wrow[CT];
+    const E *wrow[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         const int c = col0 + ct * 16 + r;
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const bf16x8 zero = {};
     const int chunks = d / 64;
     const int iters = (chunks - wave + kWaves - 1) / kWaves;   // this wave's chunks: wave, wave + 4, ...
     for (int it = 0; it < iters; ++it) {
@@ -73,8 +74,8 @@ __global__ __launch_bounds__(64 * kWaves) void gate_logits_bf16_kernel(
             const bf16x8 b1 = wrow[ct] ? *reinterpret_cast<const bf16x8 *>(wrow[ct] + k + 8) : zero;
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
-                acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[rt], b0, acc[rt][ct], 0, 0, 0);
-                acc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[rt], b1, acc[rt][ct], 0, 0, 0);
+                acc[rt][ct] = Half<E>::mfma_16x16x32(a0[rt], b0, acc[rt][ct]);
+                acc[rt][ct] = Half<E>::mfma_16x16x32(a1[rt], b1, acc[rt][ct]);
             }
         }
     }
@@ -130,10 +131,16 @@ void launch_bf16_rt(const smile_layer_desc &d, const void *x, const void *w_inte
                     float *logits_inter, float *logits_intra, int col0, hipStream_t s)
 {
     const int blocks = (d.T + kRows * RT - 1) / (kRows * RT);
-    hipLaunchKernelGGL((gate_logits_bf16_kernel<CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
-                       static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
-                       static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
-                       d.n_groups, d.m_local, col0);
+    if (d.dtype == SMILE_DTYPE_BF16)
+        hipLaunchKernelGGL((gate_logits_half_kernel<__bf16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
+                           static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
+                           static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
+                           d.n_groups, d.m_local, col0);
+    else
+        hipLaunchKernelGGL((gate_logits_half_kernel<_Float16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
+                           static_cast<const _Float16 *>(x), static_cast<const _Float16 *>(w_inter),
+                           static_cast<const _Float16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
+                           d.n_groups, d.m_local, col0);
 }
 
 // columns [col0, col0 + 16*CT)
@@ -153,7 +160,7 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
                               float *logits_inter, float *logits_intra, hipStream_t s)
 {
     const int cols = d.n_groups + d.m_local;
-    if (d.dtype == SMILE_DTYPE_BF16) {
+    if (is_half(d.dtype)) {
         // up to 128 columns per pass over x (8 accumulator tiles); wider routers (a flat one-level
         // router over all N experts) take several passes
         for (int col0 = 0; col0 < cols; col0 += 128) {

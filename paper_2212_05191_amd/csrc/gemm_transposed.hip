@@ -1,4 +1,4 @@
-// Grouped bf16 MFMA GEMM whose operands may be stored with the contraction index as the SLOW index
+// Grouped 16-bit (bf16 / fp16) MFMA GEMM whose operands may be stored with the contraction index as the SLOW index
 // ("transposed"): the four gradient GEMMs of the expert FFN backward pass,
 //
 //     dpre[r,f] = sum_c dye[r,c] W2[c,f]      x normal,      w transposed      (K = d)
@@ -36,9 +36,6 @@ namespace smile {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
@@ -78,10 +75,12 @@ __device__ __forceinline__ float activate_grad(float v)
     }
 }
 
+// E: the 16-bit storage type (__bf16 or _Float16)
+template <typename E>
 struct TGemmArgs {
-    const __bf16 *x, *w;
-    __bf16 *y;
-    const __bf16 *aux;        // POST: [N][rows][Nout] like y
+    const E *x, *w;
+    E *y;
+    const E *aux;             // POST: [N][rows][Nout] like y
     const int32_t *rows_valid;   // [N] valid output rows per group, or null: Mrows for all
     const int32_t *k_valid;      // [N] valid contraction length per group, or null: K for all
     int Mrows, Nout, K;          // output extents per group and the full contraction length
@@ -93,14 +92,14 @@ struct TGemmArgs {
 // One operand tile of a stage, as seen by the loader and by the MFMA fragment reader.
 //   T == false: [EXT rows][8 pieces], piece ^= (row >> 1) & 7
 //   T == true : [64 k][EXT / 8 pieces], piece ^= 4 * (k & 3)
-template <int EXT, bool T>
+template <typename E, int EXT, bool T>
 struct OperandTile {
     static constexpr int kPieces = EXT * BK / 8;
     static constexpr int kPiecesPerK = EXT / 8;
 
     // global source of linear LDS piece q (slab 0) and whether / how it depends on k
-    __device__ static __forceinline__ const __bf16 *source(const __bf16 *base, int q, int tile0, int ext_valid,
-                                                           int ld, int &k_row)
+    __device__ static __forceinline__ const E *source(const E *base, int q, int tile0, int ext_valid, int ld,
+                                                      int &k_row)
     {
         if constexpr (!T) {
             const int row = q >> 3, piece = (q & 7) ^ ((row >> 1) & 7);
@@ -114,14 +113,16 @@ struct OperandTile {
     }
 };
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int OCC, bool XT, bool WT, int POST>
-__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel(TGemmArgs a)
+template <typename E, int BM, int BN, int WGM, int WGN, int STAGES, int OCC, bool XT, bool WT, int POST>
+__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel(TGemmArgs<E> a)
 {
+    typedef typename Half<E>::vec8 bf16x8;                              // one MFMA operand: 8 elements
+    typedef __attribute__((__vector_size__(4 * sizeof(E)))) E bf16x4;   // 4 rounded outputs
     constexpr int NW = WGM * WGN, NT = NW * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
-    using XTile = OperandTile<BM, XT>;
-    using WTile = OperandTile<BN, WT>;
+    using XTile = OperandTile<E, BM, XT>;
+    using WTile = OperandTile<E, BN, WT>;
     constexpr int XI = XTile::kPieces / 64, WI = WTile::kPieces / 64;   // load instructions per slab
     constexpr int GPW = (XI + WI) / NW;
     constexpr int STAGE = XTile::kPieces + WTile::kPieces;
@@ -146,8 +147,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     const int kv = a.k_valid ? min(a.k_valid[e], a.K) : a.K;
     const int slabs = (kv + BK - 1) / BK;
 
-    const __bf16 *X = a.x + (size_t)e * a.sx;
-    const __bf16 *W = a.w + (size_t)e * a.sw;
+    const E *X = a.x + (size_t)e * a.sx;
+    const E *W = a.w + (size_t)e * a.sw;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     constexpr int XG = XI / NW;
     // The contraction length is ragged only in the weight-gradient GEMMs (both operands transposed).
     constexpr bool KRAGGED = XT && WT;
-    const __bf16 *src[GPW];
+    const E *src[GPW];
     int krow[GPW];
     const size_t adv_x = XT ? (size_t)BK * a.ldx : (size_t)BK, adv_w = WT ? (size_t)BK * a.ldw : (size_t)BK;
 #pragma unroll
@@ -173,10 +174,10 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
             src[i] = WTile::source(W, (inst - XI) * 64 + lane, ct * BN, a.Nout, a.ldw, krow[i]);
         }
     }
-    const __bf16 *zero = reinterpret_cast<const __bf16 *>(kZeroPiece);
+    const E *zero = reinterpret_cast<const E *>(kZeroPiece);
     // load instruction i of slab `slab` into `stage`
     auto load_one = [&](int i, int slab, int stage) {
-        const __bf16 *p = src[i] + (size_t)slab * (i < XG ? adv_x : adv_w);
+        const E *p = src[i] + (size_t)slab * (i < XG ? adv_x : adv_w);
         if (KRAGGED && slab * BK + krow[i] >= kv) p = zero;   // beyond the contraction length
         __builtin_amdgcn_global_load_lds(SMILE_GPTR(p), SMILE_LPTR(&lds[stage * STAGE + (wave + i * NW) * 64]), 16, 0, 0);
     };
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = Half<E>::mfma_32x32x16(wf[kk & 1][i], xf[kk & 1][j], acc[i][j]);
             // order inside the k-step: MFMA, LDS read(s), MFMA, ... then MFMA + global loads
             constexpr int NM = TM * TN, ND = (XT ? 2 : 1) * TM + (WT ? 2 : 1) * TN;
             constexpr int DPM = (ND + NM - 1) / NM;   // LDS reads placed after each MFMA
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
 
     // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4, row lane%32)
     // of its 32x32 tile: rounded to bf16, staged as a [OROWS][BN] tile, stored row-contiguously.
-    __bf16 *Y = a.y + (size_t)e * a.sy;
+    E *Y = a.y + (size_t)e * a.sy;
     u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
                 const int lcol = wn * WN + i * 32 + 8 * q + 4 * fhi;
                 bf16x4 out;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) out[v] = (__bf16)acc[i][j][4 * q + v];
+                for (int v = 0; v < 4; ++v) out[v] = (E)acc[i][j][4 * q + v];
                 stg[((wm * 32 + frow) * OSTRIDE) * 2 + (lcol >> 2)] = __builtin_bit_cast(u32x2, out);
             }
         }
@@ -345,15 +346,9 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
                 if constexpr (POST != 0) {
                     const u32x4 p = *reinterpret_cast<const u32x4 *>(a.aux + (size_t)e * a.sy + (size_t)row * a.Nout + col);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float lo = __uint_as_float(v[k] << 16) * activate_grad<POST>(__uint_as_float(p[k] << 16));
-                        const float hi = __uint_as_float(v[k] & 0xffff0000u) *
-                                         activate_grad<POST>(__uint_as_float(p[k] & 0xffff0000u));
-                        bf16x2 pk;
-                        pk[0] = (__bf16)lo;
-                        pk[1] = (__bf16)hi;
-                        v[k] = __builtin_bit_cast(uint32_t, pk);
-                    }
+                    for (int k = 0; k < 4; ++k)
+                        v[k] = Half<E>::pack(Half<E>::lo(v[k]) * activate_grad<POST>(Half<E>::lo(p[k])),
+                                             Half<E>::hi(v[k]) * activate_grad<POST>(Half<E>::hi(p[k])));
                 }
                 *reinterpret_cast<u32x4 *>(Y + (size_t)row * a.Nout + col) = v;
             }
@@ -361,14 +356,14 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     }
 }
 
-template <int BM, int BN, int STAGES, int OCC, bool XT, bool WT, int POST>
-hipError_t launch_tile(TGemmArgs a, int N, hipStream_t s)
+template <typename E, int BM, int BN, int STAGES, int OCC, bool XT, bool WT, int POST>
+hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
 {
     a.row_tiles = (a.Mrows + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL((grouped_gemm_t_bf16_kernel<BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
+    hipLaunchKernelGGL((grouped_gemm_t_bf16_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
                        dim3(256), 0, s, a);
     return hipGetLastError();
 }
@@ -377,34 +372,42 @@ hipError_t launch_tile(TGemmArgs a, int N, hipStream_t s)
 // workloads: two co-resident workgroups with 128 x 128 tiles and a two-stage ring beat one workgroup with a
 // larger tile or a deeper ring for all four products.  The environment variable SMILE_TGEMM_TILE (0..2)
 // overrides the choice for tuning runs.
-template <bool XT, bool WT, int POST>
-hipError_t launch_shape(const TGemmArgs &a, int N, hipStream_t s)
+template <typename E, bool XT, bool WT, int POST>
+hipError_t launch_shape(const TGemmArgs<E> &a, int N, hipStream_t s)
 {
     int tile = 2;
     if (const char *env = std::getenv("SMILE_TGEMM_TILE")) {
         const int t = std::atoi(env);
         if (t >= 0 && t <= 2) tile = t;
     }
-    if (tile == 0) return launch_tile<128, 256, 3, 1, XT, WT, POST>(a, N, s);
-    if (tile == 1) return launch_tile<128, 128, 4, 1, XT, WT, POST>(a, N, s);
-    return launch_tile<128, 128, 2, 2, XT, WT, POST>(a, N, s);
+    if (tile == 0) return launch_tile<E, 128, 256, 3, 1, XT, WT, POST>(a, N, s);
+    if (tile == 1) return launch_tile<E, 128, 128, 4, 1, XT, WT, POST>(a, N, s);
+    return launch_tile<E, 128, 128, 2, 2, XT, WT, POST>(a, N, s);
+}
+
+template <typename E>
+hipError_t launch_typed(const TransposedGemm &g, hipStream_t s)
+{
+    TGemmArgs<E> a{static_cast<const E *>(g.x), static_cast<const E *>(g.w), static_cast<E *>(g.y),
+                   static_cast<const E *>(g.aux), g.rows_valid, g.k_valid, g.Mrows, g.Nout, g.K, g.ldx, g.ldw,
+                   g.sx, g.sw, g.sy, 0, 0, 0};
+    if (g.x_transposed) return launch_shape<E, true, true, 0>(a, g.N, s);
+    if (g.post == 1) return launch_shape<E, false, true, 1>(a, g.N, s);
+    if (g.post == 2) return launch_shape<E, false, true, 2>(a, g.N, s);
+    return launch_shape<E, false, true, 0>(a, g.N, s);
 }
 
 }  // namespace
 
-hipError_t launch_grouped_gemm_t_bf16(const TransposedGemm &g, hipStream_t s)
+hipError_t launch_grouped_gemm_t(int dtype, const TransposedGemm &g, hipStream_t s)
 {
+    if (!is_half(dtype)) return hipErrorInvalidValue;
     if (g.K < 1 || g.Mrows < 1 || g.Nout % 8 || g.ldx % 8 || g.ldw % 8) return hipErrorInvalidValue;
     if (!g.x_transposed && g.K % BK) return hipErrorInvalidValue;   // a normal operand is read in whole 64-k slabs
     if (!g.w_transposed) return hipErrorInvalidValue;               // not needed by any caller
     if (g.x_transposed && (g.Mrows % 8 || g.post)) return hipErrorInvalidValue;
-    TGemmArgs a{static_cast<const __bf16 *>(g.x), static_cast<const __bf16 *>(g.w), static_cast<__bf16 *>(g.y),
-                static_cast<const __bf16 *>(g.aux), g.rows_valid, g.k_valid, g.Mrows, g.Nout, g.K, g.ldx, g.ldw,
-                g.sx, g.sw, g.sy, 0, 0, 0};
-    if (g.x_transposed) return launch_shape<true, true, 0>(a, g.N, s);
-    if (g.post == 1) return launch_shape<false, true, 1>(a, g.N, s);
-    if (g.post == 2) return launch_shape<false, true, 2>(a, g.N, s);
-    return launch_shape<false, true, 0>(a, g.N, s);
+    if (dtype == SMILE_DTYPE_BF16) return launch_typed<__bf16>(g, s);
+    return launch_typed<_Float16>(g, s);
 }
 
 }  // namespace smile

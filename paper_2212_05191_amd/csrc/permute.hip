@@ -15,7 +15,6 @@ constexpr int kPieces = 4;
 
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 // Row mapping shared by the kernels below: LPR consecutive lanes own one token row and walk its ppr
 // 16-byte pieces LPR at a time (so every access of those lanes is one contiguous run), kThreads / LPR
@@ -150,21 +149,17 @@ __global__ __launch_bounds__(kRouteBlock) void finalize_map_kernel(
     }
 }
 
-template <bool kBf16>
+// DT: storage type of the piece (SMILE_DTYPE_*)
+template <int DT>
 __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 {
     u32x4 r;
-    if constexpr (kBf16) {
+    if constexpr (DT == SMILE_DTYPE_BF16) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            // a bf16 is the upper half of an fp32
-            const float lo = __uint_as_float(v[k] << 16) * gt;
-            const float hi = __uint_as_float(v[k] & 0xffff0000u) * gt;
-            bf16x2 pk;
-            pk[0] = (__bf16)lo;   // round to nearest even
-            pk[1] = (__bf16)hi;
-            r[k] = __builtin_bit_cast(uint32_t, pk);
-        }
+        for (int k = 0; k < 4; ++k) r[k] = Half<__bf16>::pack(Half<__bf16>::lo(v[k]) * gt, Half<__bf16>::hi(v[k]) * gt);
+    } else if constexpr (DT == SMILE_DTYPE_F16) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = Half<_Float16>::pack(Half<_Float16>::lo(v[k]) * gt, Half<_Float16>::hi(v[k]) * gt);
     } else {
 #pragma unroll
         for (int k = 0; k < 4; ++k) r[k] = __float_as_uint(__uint_as_float(v[k]) * gt);
@@ -173,7 +168,7 @@ __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 }
 
 // y[t] <- gate[t] * ye[(g*m+l)*C + slot] for kept tokens, 0 for dropped ones.
-template <bool kBf16, int LPR>
+template <int DT, int LPR>
 __global__ __launch_bounds__(kThreads) void combine_kernel(
     const u32x4 *__restrict__ ye, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ slot, const float *__restrict__ gate, u32x4 *__restrict__ y,
@@ -189,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(
     }
     const float gt = gate[rl.t];
     const size_t row = (size_t)(group_idx[rl.t] * m + local_idx[rl.t]) * C + sl;
-    move_row<LPR>(ye + row * ppr, dst, ppr, rl.sub, [gt](u32x4 v) { return scale_piece<kBf16>(v, gt); });
+    move_row<LPR>(ye + row * ppr, dst, ppr, rl.sub, [gt](u32x4 v) { return scale_piece<DT>(v, gt); });
 }
 
 // lanes per row: the largest power of two <= min(ppr, 64), at least 8 (ppr >= 8 for every accepted shape... d >= 64 bf16, d >= 32 fp32)
@@ -212,7 +207,7 @@ int lanes_per_row(int ppr)
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s)
 {
-    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
@@ -224,7 +219,7 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
 hipError_t launch_dispatch_hop1(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                                 const int32_t *pos_in_group, int group_rows, void *xg, hipStream_t s)
 {
-    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop1_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
@@ -236,7 +231,7 @@ hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const
                                 const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
                                 int group_rows, void *xe, hipStream_t s)
 {
-    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop2_kernel<L>, grid, block, 0, s,
@@ -249,7 +244,7 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
                                     int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s)
 {
-    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_finalize_kernel<L>, grid, block, 0, s,
@@ -264,7 +259,7 @@ hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, c
                                const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
                                const LossArgs &loss, hipStream_t s)
 {
-    const int ppr = d.d_model * (d.dtype == SMILE_DTYPE_BF16 ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
     hipLaunchKernelGGL(finalize_map_kernel, dim3(B), dim3(kRouteBlock), 0, s, group_idx, local_idx,
                        ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group,
@@ -276,19 +271,17 @@ hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, c
 hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
                           const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s)
 {
-    const bool bf = d.dtype == SMILE_DTYPE_BF16;
-    const int ppr = d.d_model * (bf ? 2 : 4) / 16;
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    if (bf) {
-        SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<true, L>), grid, block, 0, s,
-                                                 static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
-                                                 static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity));
-    } else {
-        SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<false, L>), grid, block, 0, s,
-                                                 static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
-                                                 static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity));
-    }
+#define SMILE_COMBINE(DT)                                                                                          \
+    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<DT, L>), grid, block, 0, s,                             \
+                                             static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,       \
+                                             static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity))
+    if (d.dtype == SMILE_DTYPE_BF16) { SMILE_COMBINE(SMILE_DTYPE_BF16); }
+    else if (d.dtype == SMILE_DTYPE_F16) { SMILE_COMBINE(SMILE_DTYPE_F16); }
+    else { SMILE_COMBINE(SMILE_DTYPE_F32); }
+#undef SMILE_COMBINE
     return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@ Layout workspace_layout(const smile_layer_desc &d)
     Layout L{};
     const size_t B = ((size_t)d.T + kRouteBlock - 1) / kRouteBlock;
     const size_t N = (size_t)d.n_groups * d.m_local;
-    const size_t esz = d.dtype == SMILE_DTYPE_BF16 ? 2 : 4;
+    const size_t esz = elem_size(d.dtype);
     size_t off = 0;
     L.route_blocks = (int32_t)B;
     L.off_block_expert_hist = off; off = align_up(off + B * N * sizeof(int32_t), 256);
@@ -78,7 +78,7 @@ smile_status smile_validate_desc(const smile_layer_desc *desc)
 {
     if (!desc) return SMILE_INVALID_ARG;
     const smile_layer_desc &d = *desc;
-    if (d.dtype != SMILE_DTYPE_F32 && d.dtype != SMILE_DTYPE_BF16) return SMILE_UNSUPPORTED;
+    if (d.dtype != SMILE_DTYPE_F32 && d.dtype != SMILE_DTYPE_BF16 && d.dtype != SMILE_DTYPE_F16) return SMILE_UNSUPPORTED;
     if (d.act != SMILE_ACT_RELU && d.act != SMILE_ACT_GELU) return SMILE_UNSUPPORTED;
     if (d.T < 1 || d.d_model < 1 || d.d_ff < 1 || d.n_groups < 1 || d.m_local < 1 || d.capacity < 1)
         return SMILE_BAD_SHAPE;
@@ -86,7 +86,7 @@ smile_status smile_validate_desc(const smile_layer_desc *desc)
     const int64_t N = (int64_t)d.n_groups * d.m_local;
     if (N > 4096) return SMILE_BAD_SHAPE;
     if (d.d_model % 8 || d.d_ff % 8) return SMILE_BAD_SHAPE;
-    if (d.dtype == SMILE_DTYPE_BF16 && (d.d_model % 64 || d.d_ff % 64)) return SMILE_BAD_SHAPE;
+    if (is_half(d.dtype) && (d.d_model % 64 || d.d_ff % 64)) return SMILE_BAD_SHAPE;
     if (N * d.capacity >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
     const int64_t widest = d.d_model > d.d_ff ? d.d_model : d.d_ff;
     if ((double)N * d.capacity * (double)widest >= 1099511627776.0) return SMILE_BAD_SHAPE;

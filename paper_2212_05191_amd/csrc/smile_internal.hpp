@@ -9,6 +9,64 @@
 
 namespace smile {
 
+// bytes per element of a storage type, and whether it is one of the 16-bit types of the MFMA kernels
+inline int elem_size(int dtype) { return dtype == SMILE_DTYPE_F32 ? 4 : 2; }
+inline bool is_half(int dtype) { return dtype == SMILE_DTYPE_BF16 || dtype == SMILE_DTYPE_F16; }
+
+// The two 16-bit storage types: element, 8-element MFMA operand, the MFMA instructions, and conversion of a
+// 32-bit word holding two elements to and from fp32 (round to nearest even).
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float mfma_f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float mfma_f32x16;
+
+template <typename E>
+struct Half;
+
+template <>
+struct Half<__bf16> {
+    typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 vec8;
+    __device__ static __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }   // upper half of an fp32
+    __device__ static __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    __device__ static __forceinline__ uint32_t pack(float a, float b)
+    {
+        typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 vec2;
+        vec2 p;
+        p[0] = (__bf16)a;
+        p[1] = (__bf16)b;
+        return __builtin_bit_cast(uint32_t, p);
+    }
+    __device__ static __forceinline__ mfma_f32x16 mfma_32x32x16(vec8 a, vec8 b, mfma_f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ mfma_f32x4 mfma_16x16x32(vec8 a, vec8 b, mfma_f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <>
+struct Half<_Float16> {
+    typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 vec8;
+    typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 vec2;
+    __device__ static __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[0]; }
+    __device__ static __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[1]; }
+    __device__ static __forceinline__ uint32_t pack(float a, float b)
+    {
+        vec2 p;
+        p[0] = (_Float16)a;
+        p[1] = (_Float16)b;
+        return __builtin_bit_cast(uint32_t, p);
+    }
+    __device__ static __forceinline__ mfma_f32x16 mfma_32x32x16(vec8 a, vec8 b, mfma_f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ mfma_f32x4 mfma_16x16x32(vec8 a, vec8 b, mfma_f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+
 // tokens handled by one workgroup of the routing kernels
 constexpr int kRouteBlock = 256;
 
@@ -144,7 +202,7 @@ struct GroupedGemm {
 };
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s);
 
-// One grouped bf16 product y[e][i][j] = sum_k X(i,k) W(j,k) whose operands may have the contraction index as
+// One grouped 16-bit (bf16 / fp16) product y[e][i][j] = sum_k X(i,k) W(j,k) whose operands may have the contraction index as
 // their slow index (x_transposed: x[e] is [K][Mrows]; w_transposed: w[e] is [K][Nout]); a normal x is
 // [Mrows][K].  ldx / ldw: leading dimensions, sx / sw / sy: per-group strides, all in elements.
 // rows_valid[e] (or Mrows) output rows are computed; k_valid[e] (or K) terms are summed (transposed operands
@@ -159,7 +217,7 @@ struct TransposedGemm {
     bool x_transposed, w_transposed;
     int post;
 };
-hipError_t launch_grouped_gemm_t_bf16(const TransposedGemm &g, hipStream_t s);
+hipError_t launch_grouped_gemm_t(int dtype, const TransposedGemm &g, hipStream_t s);
 
 // Last routing step for the fully fused forward pass: pos_in_group / slot as launch_route's finalize
 // kernel, plus the slot -> token map in ws.slot_token, zero output rows for dropped tokens in y, and

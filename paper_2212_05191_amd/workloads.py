@@ -69,6 +69,8 @@ EXTRA_CONFIGS = {
     # cfg4 with the flat one-level router the paper compares against (Switch Transformer: Section 2,
     # Eq. 1-2 with k = 1): same tokens, experts and capacity, one 128-way gate instead of 16 x 8
     "cfg4_flat": LayerConfig("cfg4_flat", 32768, 768, 3072, 1, 128, 1.0, 256, "bf16", "gelu", seed=4),
+    # cfg2 stored in IEEE half precision, the precision the paper trains in (Section 4.1)
+    "cfg2_f16": LayerConfig("cfg2_f16", 8192, 768, 3072, 2, 8, 1.0, 512, "f16", "gelu", seed=2),
 }
 
 

@@ -60,6 +60,9 @@ def test_validate_desc_accepts_the_five_configs():
         assert B.smile_workspace_bytes(d) > 0
         d.group_capacity = 7
         assert B.smile_validate_desc(d) == B.OK
+        if cfg.dtype == "bf16":
+            d.dtype = B.DTYPE["f16"]
+            assert B.smile_validate_desc(d) == B.OK
 
 
 def test_desc_layout_matches_the_header():
@@ -76,6 +79,7 @@ def test_desc_layout_matches_the_header():
     (dict(T=0), B.BAD_SHAPE), (dict(capacity=0), B.BAD_SHAPE), (dict(n_groups=0), B.BAD_SHAPE),
     (dict(m_local=-1), B.BAD_SHAPE), (dict(d_model=60), B.BAD_SHAPE), (dict(d_ff=100), B.BAD_SHAPE),
     (dict(dtype="bf16", d_model=72), B.BAD_SHAPE), (dict(dtype="bf16", d_ff=96), B.BAD_SHAPE),
+    (dict(dtype="f16", d_model=72), B.BAD_SHAPE),
     (dict(n_groups=2048), B.BAD_SHAPE), (dict(n_groups=128, m_local=64), B.BAD_SHAPE),
     (dict(capacity=2 ** 30, n_groups=4), B.BAD_SHAPE),
     (dict(dtype=7), B.UNSUPPORTED), (dict(act=3), B.UNSUPPORTED),

@@ -147,6 +147,8 @@ BACKWARD_CASES = [
     wl.small_config("bwd_bf16_empty_experts", 40, 64, 128, 4, 4, 8, "bf16", "gelu", seed=51),
     # contraction lengths of the weight-gradient GEMMs from 0 to several 64-row slabs with ragged ends
     wl.small_config("bwd_bf16_long_ragged", 4099, 128, 256, 2, 4, 700, "bf16", "gelu", skew=True, seed=52),
+    wl.small_config("bwd_f16_gelu", 3000, 192, 320, 3, 4, 200, "f16", "gelu", seed=53),
+    wl.small_config("bwd_f16_relu_skew", 2500, 128, 448, 4, 8, 90, "f16", "relu", skew=True, seed=54),
 ]
 
 
@@ -223,7 +225,8 @@ def test_backward_full_size_sampled(torch_cuda, name):
         layer.close()
 
 
-@pytest.mark.parametrize("cfg", [BACKWARD_CASES[1], BACKWARD_CASES[3], BACKWARD_CASES[4]], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [BACKWARD_CASES[1], BACKWARD_CASES[3], BACKWARD_CASES[4], BACKWARD_CASES[12]],
+                         ids=lambda c: c.name)
 def test_saved_activations_equal_recomputation(torch_cuda, cfg):
     """Forward pass that also stores h and the pre-activation, backward pass that reads them: the forward
     outputs and every gradient are bit-identical to the path that recomputes them."""

@@ -77,6 +77,11 @@ SMALL = [
                     group_capacity=1100),
     wl.small_config("group_cap_loose", 900, 64, 64, 2, 3, 120, "bf16", "gelu", seed=32, group_capacity=900),
     wl.small_config("group_cap_one_row", 300, 64, 64, 5, 2, 4, "bf16", "relu", seed=33, group_capacity=1),
+    # half precision, the precision the paper trains in (Section 4.1)
+    wl.small_config("mid_f16_gelu", 3000, 192, 320, 3, 4, 200, "f16", "gelu", seed=34),
+    wl.small_config("f16_relu_skew_group_cap", 2500, 128, 448, 4, 8, 90, "f16", "relu", skew=True, seed=35,
+                    group_capacity=800),
+    wl.small_config("f16_flat_200", 4000, 64, 128, 1, 200, 30, "f16", "gelu", seed=36),
 ]
 
 
@@ -107,6 +112,7 @@ def test_chained_entry_point_equals_step_by_step(torch_cuda, cfg):
 
 
 FUSED_CASES = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[6], SMALL[10], SMALL[16], SMALL[17], SMALL[19],
+               SMALL[20], SMALL[21],
                wl.small_config("fused_ragged", 4099, 128, 256, 4, 8, 100, "bf16", "gelu", skew=True, seed=26)]
 
 
@@ -226,11 +232,11 @@ def test_expert_biases(torch_cuda):
         layer.close()
 
 
-@pytest.mark.parametrize("tile", list(range(7)))
-def test_every_ffn_tile_shape(torch_cuda, tile, monkeypatch):
+@pytest.mark.parametrize("tile,dtype", [(t, "bf16") for t in range(7)] + [(0, "f16"), (2, "f16"), (6, "f16")])
+def test_every_ffn_tile_shape(torch_cuda, tile, dtype, monkeypatch):
     """Each MFMA tile shape of the grouped GEMM, on a shape with ragged row and column tiles."""
     monkeypatch.setenv("SMILE_FFN_TILE", str(tile))
-    cfg = wl.small_config(f"tile{tile}", 4000, 320, 448, 2, 3, 600, "bf16", "gelu", seed=23)
+    cfg = wl.small_config(f"tile{tile}_{dtype}", 4000, 320, 448, 2, 3, 600, dtype, "gelu", seed=23)
     layer = _run(cfg)
     try:
         _say(f"   {parity.check_full(cfg, layer)}")
@@ -247,7 +253,7 @@ def test_cfg2_full_parity(torch_cuda):
         layer.close()
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5", "t2_48b", "cfg5_group_cap"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5", "t2_48b", "cfg5_group_cap", "cfg2_f16"])
 def test_full_size_configs_sampled_parity(torch_cuda, name):
     if name == "cfg5_group_cap":
         # cfg5 with a first-hop buffer of 1.25 x the mean group load: its Zipf-skewed groups overflow it
