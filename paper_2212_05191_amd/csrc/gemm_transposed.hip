@@ -20,8 +20,9 @@
 //     k-row (i / 4) [+4 for the second read] and the 4-column block (i % 4) of its 16-column span,
 //     and every lane ends up with k, k+1, k+2, k+3 of its own column -- the same k order as a
 //     normal operand, so the two kinds mix in one MFMA.
-//   * transposed tiles are swizzled by k: piece ^= 4 * (k & 3).  The 8 k-rows a wave touches in one
-//     read then cover all 64 banks twice, the minimum for 512 bytes.
+//   * transposed tiles are swizzled by k: a row's pieces are rotated by 4 * (k & 3) positions.  The 8
+//     k-rows a wave touches in one read then cover all 64 banks twice, the minimum for 512 bytes
+//     (rows of 16, 24 or 32 pieces alike; with 24 the last group of four pieces wraps onto a used bank).
 //   * the contraction length of the weight-gradient GEMMs is the expert's row count: slabs beyond it
 //     are skipped, and k-rows beyond it inside the last slab are loaded from a zero block instead
 //     (no zero-padded copies, no work on empty buffer rows).
@@ -91,7 +92,7 @@ struct TGemmArgs {
 
 // One operand tile of a stage, as seen by the loader and by the MFMA fragment reader.
 //   T == false: [EXT rows][8 pieces], piece ^= (row >> 1) & 7
-//   T == true : [64 k][EXT / 8 pieces], piece ^= 4 * (k & 3)
+//   T == true : [64 k][EXT / 8 pieces], position = (piece + 4 * (k & 3)) mod (EXT / 8)
 template <typename E, int EXT, bool T>
 struct OperandTile {
     static constexpr int kPieces = EXT * BK / 8;
@@ -106,7 +107,8 @@ struct OperandTile {
             k_row = -1;   // all k of this piece are inside the slab; no k bound needed (K % 64 == 0)
             return base + (size_t)min(tile0 + row, ext_valid - 1) * ld + piece * 8;
         } else {
-            const int k = q / kPiecesPerK, piece = (q - k * kPiecesPerK) ^ (4 * (k & 3));
+            const int k = q / kPiecesPerK, pos = q - k * kPiecesPerK;
+            const int piece = pos - 4 * (k & 3) + (pos < 4 * (k & 3) ? kPiecesPerK : 0);   // the piece rotated to pos
             k_row = k;
             return base + (size_t)k * ld + min(tile0 + piece * 8, ext_valid - 8);
         }
@@ -128,8 +130,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     constexpr int STAGE = XTile::kPieces + WTile::kPieces;
     constexpr int OROWS = WGM * 32, OSTRIDE = BN / 8 + 1, OPR = BN / 8;
     static_assert((XI + WI) % NW == 0, "load instructions must divide over the waves");
-    static_assert(!XT || (BM & (BM - 1)) == 0, "a transposed tile needs a power-of-two extent (XOR swizzle)");
-    static_assert(!WT || (BN & (BN - 1)) == 0, "a transposed tile needs a power-of-two extent (XOR swizzle)");
+    static_assert(BM % 32 == 0 && BN % 32 == 0 && BM >= 128 && BN >= 128, "rotation swizzle: rows of at least 16 pieces");
     static_assert(STAGES >= 2 && STAGES <= 4 && (STAGES - 2) * GPW < 64, "pipeline depth");
     static_assert(OROWS * OSTRIDE <= STAGES * STAGE, "epilogue staging must fit in the pipeline buffers");
 
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     for (int j = 0; j < TM; ++j) {
         if constexpr (XT) {
             const int col = wm * WM + j * 32 + tcol;
-            xoff[j] = (tk0 * XTile::kPiecesPerK + ((col >> 3) ^ (4 * tj))) * 16 + (col & 4) * 2;
+            xoff[j] = (tk0 * XTile::kPiecesPerK + ((col >> 3) + 4 * tj) % XTile::kPiecesPerK) * 16 + (col & 4) * 2;
         } else {
             xoff[j] = ((wm * WM + j * 32 + frow) * 8) * 16;
         }
@@ -208,7 +209,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel
     for (int i = 0; i < TN; ++i) {
         if constexpr (WT) {
             const int col = wn * WN + i * 32 + tcol;
-            woff[i] = (XTile::kPieces + tk0 * WTile::kPiecesPerK + ((col >> 3) ^ (4 * tj))) * 16 + (col & 4) * 2;
+            woff[i] = (XTile::kPieces + tk0 * WTile::kPiecesPerK + ((col >> 3) + 4 * tj) % WTile::kPiecesPerK) * 16 +
+                      (col & 4) * 2;
         } else {
             woff[i] = ((XTile::kPieces + (wn * WN + i * 32 + frow) * 8)) * 16;
         }
@@ -369,20 +371,23 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
 }
 
 // Tile shapes: id -> (BM, BN, stages, workgroups per CU).  Measured on the backward pass of the bf16
-// workloads: two co-resident workgroups with 128 x 128 tiles and a two-stage ring beat one workgroup with a
-// larger tile or a deeper ring for all four products.  The environment variable SMILE_TGEMM_TILE (0..2)
-// overrides the choice for tuning runs.
+// workloads: two co-resident workgroups with a two-stage ring beat one workgroup with a larger tile or a
+// deeper ring for all four products; 128 x 192 (fewer LDS bytes per MFMA) wins when it still gives every CU
+// its two workgroups, else 128 x 128.  The environment variable SMILE_TGEMM_TILE (0..3) overrides the choice
+// for tuning runs.
 template <typename E, bool XT, bool WT, int POST>
 hipError_t launch_shape(const TGemmArgs<E> &a, int N, hipStream_t s)
 {
-    int tile = 2;
+    const long long wide = (long long)N * ((a.Mrows + 127) / 128) * ((a.Nout + 191) / 192);
+    int tile = wide >= 512 ? 3 : 2;
     if (const char *env = std::getenv("SMILE_TGEMM_TILE")) {
         const int t = std::atoi(env);
-        if (t >= 0 && t <= 2) tile = t;
+        if (t >= 0 && t <= 3) tile = t;
     }
     if (tile == 0) return launch_tile<E, 128, 256, 3, 1, XT, WT, POST>(a, N, s);
     if (tile == 1) return launch_tile<E, 128, 128, 4, 1, XT, WT, POST>(a, N, s);
-    return launch_tile<E, 128, 128, 2, 2, XT, WT, POST>(a, N, s);
+    if (tile == 2) return launch_tile<E, 128, 128, 2, 2, XT, WT, POST>(a, N, s);
+    return launch_tile<E, 128, 192, 2, 2, XT, WT, POST>(a, N, s);
 }
 
 template <typename E>

@@ -186,6 +186,19 @@ def test_chained_backward_equals_steps_and_repeats(torch_cuda, cfg):
         b.close()
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+def test_every_gradient_gemm_tile_shape(torch_cuda, tile, monkeypatch):
+    """Each tile shape of the transposed-operand GEMM on a shape with ragged tiles in every direction."""
+    monkeypatch.setenv("SMILE_TGEMM_TILE", str(tile))
+    cfg = wl.small_config(f"bwd_tile{tile}", 2600, 320, 448, 2, 3, 500, "bf16", "gelu", seed=55)
+    layer = _forward_backward(cfg)
+    try:
+        _, _, info = _check_steps(cfg, layer)
+        _say(f"   {({k: float(f'{v:.2e}') for k, v in info.items()})}")
+    finally:
+        layer.close()
+
+
 def test_backward_large_aux_coefficients(torch_cuda):
     """Eq. 4 terms large enough to dominate the router gradients (the default 0.005 hides them below the gate term)."""
     from paper_2212_05191_amd.runner import GpuLayer
