@@ -27,10 +27,10 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM bytes per launch of the dominant kernel (up-projection GEMM) from the two rocprofv3 --pmc passes
-# summarised in profiles/bench_cfg2_hbm_traffic_pmc.txt: FETCH_SIZE 43047.0 KiB x 1.99981 + WRITE_SIZE
+# summarised in profiles/bench_cfg2_hbm_traffic_pmc.txt: FETCH_SIZE 43040.8 KiB x 1.99981 + WRITE_SIZE
 # 48024.0 KiB x 1.00000 (scale factors = what the same counters read for a plain 256 MiB device copy).
 # Measured for the headline workload only.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 137.33e6}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 137.32e6}
 
 
 def main():
