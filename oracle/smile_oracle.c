@@ -23,7 +23,7 @@
  *     that the layer stores (hidden activation h, expert output, layer output)
  *     are rounded to that type (nearest, ties to even) where they would be stored.
  *
- * Readings of points the paper leaves open (all listed in the design notes):
+ * Readings of points the paper leaves open:
  *   - Eq. 1 is read as a softmax, as the sentence introducing it says.
  *   - One inter router W_p[n,d] and ONE intra router W_q[m,d] shared by all
  *     groups ("tied parameters", router size O(m+n), Section 3.2.1).

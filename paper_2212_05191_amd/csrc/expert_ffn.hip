@@ -406,7 +406,7 @@ hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t
 }
 
 // Tile shapes: id -> (BM, BN, waves along M, waves along N, BK, stages, waves/SIMD budget).
-// Measured on the four bf16 workloads (T = 8192..65536, 16..256 experts, see the design notes):
+// Measured on the four bf16 workloads (T = 8192..65536 tokens, 16..256 experts):
 //   * up-projection (short K = d_model, wide output, GELU epilogue): 128x192 with two stages and two
 //     co-resident workgroups per CU wins everywhere -- the second workgroup's MFMAs cover the first
 //     one's prologue latency and activation epilogue;
