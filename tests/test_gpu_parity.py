@@ -46,7 +46,7 @@ def _run(cfg, forward="steps", **kw):
         layer.forward_steps()
     elif forward == "fused":
         layer.forward_fused()
-    else:
+    elif forward != "none":
         layer.forward()
     return layer
 
@@ -204,6 +204,44 @@ def test_repeated_calls_are_bit_identical(torch_cuda):
                 np.testing.assert_array_equal(first[k], again[k], err_msg=k)
     finally:
         layer.close()
+
+
+def test_work_runs_on_the_callers_stream(torch_cuda):
+    """Every entry point enqueues on the stream it is given: a forward + backward pass issued on a side stream
+    (default priority) behind a long-running kernel of that stream gives the same bits as on the default stream."""
+    torch = torch_cuda
+    cfg = wl.small_config("side_stream", 3000, 128, 256, 3, 4, 300, "bf16", "gelu", skew=True, seed=37)
+    a = _run(cfg, "chained")
+    a.prepare_backward(wl.gen_output_grad(cfg))
+    a.backward()
+    b = _run(cfg, "none")
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            # something long in front: if the library launched on another stream it would race with the fill below
+            big = torch.empty(256 << 20, dtype=torch.uint8, device=b.x.device)
+            for _ in range(4):
+                big.fill_(1)
+            b.buf.y.fill_(-77)
+            b.forward_steps()
+            b.prepare_backward(wl.gen_output_grad(cfg))
+            b.backward_steps()
+        side.synchronize()
+        oa, ob = parity.fetch(a), parity.fetch(b)
+        kept = oa["kept_count"]
+        mask = np.arange(cfg.capacity)[None, :] < kept[:, None]
+        for k in oa:
+            if k in ("xe", "ye"):
+                np.testing.assert_array_equal(oa[k][mask], ob[k][mask], err_msg=k)
+            else:
+                np.testing.assert_array_equal(oa[k], ob[k], err_msg=k)
+        from paper_2212_05191_amd.runner import to_host
+        for k in ("dx", "dw1", "dw2", "dw_inter", "dw_intra", "dgate"):
+            np.testing.assert_array_equal(to_host(getattr(a.bwd, k)), to_host(getattr(b.bwd, k)), err_msg=k)
+    finally:
+        a.close()
+        b.close()
 
 
 def test_expert_biases(torch_cuda):
