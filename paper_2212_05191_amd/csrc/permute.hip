@@ -150,6 +150,104 @@ __global__ __launch_bounds__(kRouteBlock) void finalize_map_kernel(
 }
 
 // DT: storage type of the piece (SMILE_DTYPE_*)
+// finalize_map for small batches (at most 64 routing blocks), with the scan of the per-block histograms
+// folded in (no scan kernel ran).  One wave per histogram column, one lane per earlier block: block b gets its
+// exclusive offsets as a masked wave sum.  The totals are spread over two otherwise idle ends of the grid: the
+// last block writes the expert counts (its offsets + its own row), block 0 the group / local counts, the
+// probability sums (same summation order as the scan kernel: identical bits) and the loss.
+// Dynamic LDS: [N + n] offsets, then [n] + [m] counts and [n] + [m] sums.
+__global__ __launch_bounds__(kRouteBlock) void finalize_map_scan_kernel(
+    const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
+    const int32_t *__restrict__ block_expert_hist, const int32_t *__restrict__ block_group_hist,
+    const float *__restrict__ block_p_sum, const float *__restrict__ block_q_sum,
+    const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
+    int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, int32_t *__restrict__ slot_token,
+    u32x4 *__restrict__ y, int T, int ppr, int n, int m, int C,
+    int32_t *__restrict__ group_count, int32_t *__restrict__ local_count, int32_t *__restrict__ expert_count,
+    int32_t *__restrict__ kept_count, float *__restrict__ p_sum, float *__restrict__ q_sum,
+    float *__restrict__ loss3, float alpha, float beta)
+{
+    extern __shared__ int32_t lds_i[];
+    const int N = n * m, B = gridDim.x, b = blockIdx.x, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    constexpr int kWaves = kRouteBlock / 64;
+    int32_t *eoff = lds_i, *goff = lds_i + N;
+    // lane = earlier block (B <= 64); two columns per iteration so that their loads overlap
+    for (int c = wave; c < N + n; c += 2 * kWaves) {
+        const int c2 = c + kWaves;
+        int v0 = 0, v1 = 0;
+        if (lane < b) {
+            v0 = c < N ? block_expert_hist[(size_t)lane * N + c] : block_group_hist[(size_t)lane * n + (c - N)];
+            if (c2 < N + n)
+                v1 = c2 < N ? block_expert_hist[(size_t)lane * N + c2] : block_group_hist[(size_t)lane * n + (c2 - N)];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            v0 += __shfl_xor(v0, off, 64);
+            v1 += __shfl_xor(v1, off, 64);
+        }
+        if (lane == 0) {
+            lds_i[c] = v0;
+            if (c2 < N + n) lds_i[c2] = v1;
+        }
+    }
+    __syncthreads();
+
+    const int t = b * kRouteBlock + tid;
+    bool dropped = false;
+    if (t < T) {
+        const int g = group_idx[t], e = g * m + local_idx[t];
+        const int rank = eoff[e] + rank_in_block[t];
+        const int sl = rank < C ? rank : -1;
+        slot[t] = sl;
+        pos_in_group[t] = goff[g] + pos_in_block[t];
+        if (sl >= 0) slot_token[(size_t)e * C + sl] = t;
+        dropped = sl < 0;
+    }
+    unsigned long long mask = __ballot(dropped);
+    const int t0 = t - lane;
+    while (mask) {
+        const int src = __ffsll((long long)mask) - 1;
+        u32x4 *row = y + (size_t)(t0 + src) * ppr;
+        for (int p = lane; p < ppr; p += 64) row[p] = u32x4{0u, 0u, 0u, 0u};
+        mask &= mask - 1;
+    }
+
+    if (b == B - 1) {   // expert totals = offsets of the last block + its own histogram row
+        for (int e = tid; e < N; e += kRouteBlock) {
+            const int total = eoff[e] + block_expert_hist[(size_t)b * N + e];
+            expert_count[e] = total;
+            kept_count[e] = min(total, C);
+        }
+    }
+    if (b != 0) return;
+
+    // ---- block 0: one wave per column of [n group counts | m local counts | n p sums | m q sums], then the loss
+    int32_t *cnt_g = lds_i + N + n, *cnt_l = cnt_g + n;
+    float *sum_p = reinterpret_cast<float *>(cnt_l + m), *sum_q = sum_p + n;
+    for (int c = wave; c < 2 * (n + m); c += kWaves) {
+        if (c < n + m) {
+            const int32_t *col = c < n ? block_group_hist + c : block_group_hist + (size_t)B * n + (c - n);
+            const int stride = c < n ? n : m;
+            int sum = lane < B ? col[(size_t)lane * stride] : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+            if (lane == 0) {
+                if (c < n) { cnt_g[c] = sum; group_count[c] = sum; }
+                else { cnt_l[c - n] = sum; local_count[c - n] = sum; }
+            }
+        } else if (c < 2 * n + m) {
+            const float v = wave_sum_column(block_p_sum, B, n, c - n - m);
+            if (lane == 0) { sum_p[c - n - m] = v; p_sum[c - n - m] = v; }
+        } else {
+            const float v = wave_sum_column(block_q_sum, B, m, c - 2 * n - m);
+            if (lane == 0) { sum_q[c - 2 * n - m] = v; q_sum[c - 2 * n - m] = v; }
+        }
+    }
+    __syncthreads();
+    if (loss3 && tid < 64) aux_loss_wave(cnt_g, cnt_l, sum_p, sum_q, T, n, m, alpha, beta, loss3);
+}
+
 template <int DT>
 __device__ __forceinline__ u32x4 scale_piece(u32x4 v, float gt)
 {
@@ -265,6 +363,23 @@ hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, c
                        ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group,
                        slot, ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr, d.n_groups, d.m_local, d.capacity, loss,
                        d.alpha, d.beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_map_scan(const smile_layer_desc &d, const Workspace &ws, const int32_t *group_idx,
+                                    const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
+                                    int32_t *group_count, int32_t *local_count, int32_t *expert_count,
+                                    int32_t *kept_count, float *p_sum, float *q_sum, float *loss3, hipStream_t s)
+{
+    const int ppr = d.d_model * elem_size(d.dtype) / 16;
+    const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
+    const int n = d.n_groups, m = d.m_local;
+    const size_t lds = sizeof(int32_t) * (size_t)(n * m + n + 2 * (n + m));
+    hipLaunchKernelGGL(finalize_map_scan_kernel, dim3(B), dim3(kRouteBlock), lds, s, group_idx, local_idx,
+                       ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum, ws.rank_in_block,
+                       ws.pos_in_block, pos_in_group, slot, ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr, n, m,
+                       d.capacity, group_count, local_count, expert_count, kept_count, p_sum, q_sum, loss3, d.alpha,
+                       d.beta);
     return hipGetLastError();
 }
 

@@ -222,17 +222,6 @@ __device__ __forceinline__ int wave_scan_column(int32_t *__restrict__ hist, int 
     return carry;
 }
 
-// Sum over blocks of one column of per-block partial sums, in a fixed order: lane l adds blocks
-// l, l+64, ... serially, then a fixed butterfly over the wave.
-__device__ __forceinline__ float wave_sum_column(const float *__restrict__ part, int B, int stride, int col)
-{
-    float s = 0.f;
-    for (int b = __lane_id(); b < B; b += 64) s += part[(size_t)b * stride + col];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    return s;
-}
-
 // One wave per column of the work list
 //   [N expert columns | n group columns | n p-sum columns | m q-sum columns | m local-count columns],
 // 4 waves per workgroup; the columns are independent, so the grid spreads them over the chip.
@@ -359,7 +348,7 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
                         int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
-                        bool finalize)
+                        bool finalize, bool scan)
 {
     const int n = d.n_groups, m = d.m_local, N = n * m;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
@@ -369,7 +358,7 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
                        ws.pos_in_block, ws.rank_in_block, gate, p_top, q_top, ws.block_expert_hist,
                        ws.block_group_hist, ws.block_p_sum, ws.block_q_sum);
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess || !scan) return err;   // !scan: the caller's last step scans the histograms itself
     const int columns = N + 2 * n + 2 * m;
     hipLaunchKernelGGL(route_scan_kernel, dim3((columns + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0, s, B, n,
                        m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,

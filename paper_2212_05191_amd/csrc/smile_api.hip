@@ -293,14 +293,21 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool fused = io->xe == nullptr;
     const LossArgs loss{io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3};
+    // small batches: the fused path's last routing kernel scans the few per-block histograms itself
+    const int route_blocks = (d.T + kRouteBlock - 1) / kRouteBlock;
+    const bool scan_in_finalize = fused && d.group_capacity == 0 && route_blocks <= kScanInFinalizeBlocks;
     hipError_t err = launch_gate_logits(d, io->x, io->w_inter, io->w_intra, io->logits_inter, io->logits_intra, s);
     if (err == hipSuccess)
         err = launch_route(d, ctx->ws, io->logits_inter, io->logits_intra, io->bias_inter, io->bias_intra,
                            io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->gate, io->p_top, io->q_top,
                            io->group_count, io->local_count, io->expert_count, io->kept_count, io->p_sum, io->q_sum,
-                           s, /*finalize=*/false);
+                           s, /*finalize=*/false, /*scan=*/!scan_in_finalize);
     if (fused) {
-        if (err == hipSuccess)
+        if (err == hipSuccess && scan_in_finalize)
+            err = launch_finalize_map_scan(d, ctx->ws, io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->y,
+                                           io->group_count, io->local_count, io->expert_count, io->kept_count,
+                                           io->p_sum, io->q_sum, io->loss3, s);
+        else if (err == hipSuccess)
             err = launch_finalize_map(d, ctx->ws, io->group_idx, io->local_idx, io->pos_in_group, io->slot, io->y,
                                       loss, s);
         if (err == hipSuccess)

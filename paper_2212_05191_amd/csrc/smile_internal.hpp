@@ -120,6 +120,17 @@ __device__ __forceinline__ void aux_loss_wave(const int32_t *group_count, const 
     }
 }
 
+// Sum over blocks of one column of per-block partial sums, in a fixed order: lane l adds blocks
+// l, l+64, ... serially, then a fixed butterfly over the wave.
+__device__ __forceinline__ float wave_sum_column(const float *__restrict__ part, int B, int stride, int col)
+{
+    float s = 0.f;
+    for (int b = __lane_id(); b < B; b += 64) s += part[(size_t)b * stride + col];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+}
+
 }  // namespace smile
 
 struct smile_ctx {
@@ -143,13 +154,15 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
                               float *logits_inter, float *logits_intra, hipStream_t s);
 
 // finalize = false leaves pos_in_group / slot unwritten (the block-local ranks stay in the workspace
-// for launch_dispatch_finalize).
+// for launch_dispatch_finalize).  scan = false (needs finalize = false, no group capacity) also leaves the
+// per-block histograms and partial sums unscanned and the counts / sums unwritten: launch_finalize_map_scan
+// does both.
 hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const float *logits_inter,
                         const float *logits_intra, const float *bias_inter, const float *bias_intra,
                         int32_t *group_idx, int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, float *gate,
                         float *p_top, float *q_top, int32_t *group_count, int32_t *local_count,
                         int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum, hipStream_t s,
-                        bool finalize = true);
+                        bool finalize = true, bool scan = true);
 
 hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32_t *group_idx,
                            const int32_t *local_idx, const int32_t *slot, void *xe, hipStream_t s);
@@ -250,6 +263,15 @@ hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, 
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s);
 hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspace, const void *x, const float *dlp,
                                         const float *dlq, float *dw_inter, float *dw_intra, hipStream_t s);
+
+// The same for small batches, without the separate scan kernel: every block sums the histogram rows of the
+// blocks before it (at most kScanInFinalizeBlocks - 1 rows), and the last block produces the counts, the
+// probability sums (same summation order as the scan kernel: identical bits) and the loss.
+constexpr int kScanInFinalizeBlocks = 64;
+hipError_t launch_finalize_map_scan(const smile_layer_desc &d, const Workspace &ws, const int32_t *group_idx,
+                                    const int32_t *local_idx, int32_t *pos_in_group, int32_t *slot, void *y,
+                                    int32_t *group_count, int32_t *local_count, int32_t *expert_count,
+                                    int32_t *kept_count, float *p_sum, float *q_sum, float *loss3, hipStream_t s);
 
 hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
                            const float *p_sum, const float *q_sum, float *out3, hipStream_t s);
