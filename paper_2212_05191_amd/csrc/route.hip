@@ -1,11 +1,12 @@
 // Bi-level top-1 routing with per-expert capacity (Section 3.2.1, Section 3.2.2 statistics,
 // Section 4.2 capacity), as three small kernels:
 //
-//   route_decide   one thread per token: biased logits -> top-1 group and local expert, the two
-//                  softmax probabilities (Eq. 1 read as a softmax), the gate p*q (Eq. 3); per-block
-//                  column sums of p and q; the token's rank among EARLIER tokens of the same block
-//                  with the same group / the same expert (wave64 ballots + LDS counters); per-block
-//                  histograms.
+//   route_decide   one thread per token: biased logits (both rows fetched at once and kept in registers
+//                  for routers of up to 32 columns) -> top-1 group and local expert, the two softmax
+//                  probabilities (Eq. 1 read as a softmax), the gate p*q (Eq. 3); per-block column sums
+//                  of p and q (wave butterflies, then the waves in order); the token's rank among
+//                  EARLIER tokens of the same block with the same group / the same expert (wave64
+//                  ballots + per-wave LDS counters combined after one barrier); per-block histograms.
 //   route_scan     one wave per histogram column: exclusive scan along the block axis (turning the
 //                  histograms into block offsets; 64 blocks per shuffle scan), totals, kept counts,
 //                  and the fixed-order sums of p and q.
@@ -20,13 +21,13 @@
 // Everything that decides an integer is integer arithmetic or an fp32 compare of the caller's logits,
 // so the result depends only on the logits and the token order, never on the launch geometry.  No
 // atomics order, no inter-workgroup waiting, no memory that must be cleared beforehand.
+#include <algorithm>
+
 #include "smile_internal.hpp"
 
 namespace smile {
 
 namespace {
-
-constexpr int kColChunk = 32;   // probability columns summed per LDS pass
 
 __device__ __forceinline__ unsigned long long lanemask_lt()
 {
@@ -95,40 +96,99 @@ __device__ __forceinline__ void top1_softmax(const float *__restrict__ row, cons
     inv_z = 1.0f / z;
 }
 
-// Column sums over the block's tokens of prob[t, c] = exp(a[t,c] - mx_t) * inv_z_t, written to
-// out[c], in a fixed order: 8 segments of 32 tokens summed serially, then the 8 partials serially.
-__device__ __forceinline__ void block_column_sums(const float *__restrict__ row, const float *__restrict__ bias,
-                                                  int len, float mx, float inv_z, bool valid,
-                                                  float (*tile)[kColChunk + 1], float (*part)[kColChunk],
-                                                  float *__restrict__ out)
+// A whole logit row kept in registers (routers of up to CAP columns): every load is issued before the first
+// use, and the argmax, the exp-sum and the per-column probabilities all come from the same registers, so a
+// token waits for memory once per router instead of once per pass.  Columns >= len hold -inf.
+template <int CAP>
+__device__ __forceinline__ void load_row(const float *__restrict__ row, const float *__restrict__ bias, int len,
+                                         float (&a)[CAP])
 {
-    const int tid = threadIdx.x;
-    for (int c0 = 0; c0 < len; c0 += kColChunk) {
-        const int w = min(kColChunk, len - c0);
-        for (int i0 = 0; i0 < w; i0 += kLoadChunk) {
-            float a[kLoadChunk];
-            if (valid) load_biased(row, bias, c0 + i0, len, -INFINITY, a);
+    float v[CAP], bv[CAP];
 #pragma unroll
-            for (int k = 0; k < kLoadChunk; ++k)
-                if (i0 + k < w) tile[tid][i0 + k] = valid ? exp_neg(a[k] - mx) * inv_z : 0.f;
-        }
-        __syncthreads();
-        const int col = tid & (kColChunk - 1), seg = tid / kColChunk;   // 8 segments of 32 tokens
-        if (col < w) {
-            float s = 0.f;
-            for (int j = 0; j < kRouteBlock / 8; ++j) s += tile[seg * (kRouteBlock / 8) + j][col];
-            part[seg][col] = s;
-        }
-        __syncthreads();
-        if (tid < w) {
-            float s = 0.f;
-            for (int sg = 0; sg < 8; ++sg) s += part[sg][tid];
-            out[c0 + tid] = s;
-        }
-        __syncthreads();
+    for (int k = 0; k < CAP; ++k) {
+        const int i = min(k, len - 1);
+        v[k] = row[i];
+        bv[k] = bias ? bias[i] : 0.f;
     }
+#pragma unroll
+    for (int k = 0; k < CAP; ++k) a[k] = k < len ? (bias ? __fadd_rn(v[k], bv[k]) : v[k]) : -INFINITY;
 }
 
+template <int CAP>
+__device__ __forceinline__ void top1_softmax_row(const float (&a)[CAP], int &arg, float &mx, float &inv_z)
+{
+    arg = 0;
+    mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < CAP; ++k)
+        if (a[k] > mx) { mx = a[k]; arg = k; }   // strict: the lowest index of the maximum wins
+    float z = 0.f;
+#pragma unroll
+    for (int k = 0; k < CAP; ++k) z += exp_neg(a[k] - mx);   // exp2(-inf) = 0 for the padding
+    inv_z = 1.0f / z;
+}
+
+// block_column_sums (below) on a row held in registers
+template <int CAP>
+__device__ __forceinline__ void block_column_sums_row(const float (&a)[CAP], int len, float mx, float inv_z, bool valid,
+                                                      float *__restrict__ part, float *__restrict__ out)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int k = 0; k < CAP; ++k) {
+        if (k < len) {   // uniform
+            float v = valid ? exp_neg(a[k] - mx) * inv_z : 0.f;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0) part[wave * len + k] = v;
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < len; c += kRouteBlock) {
+        float sum = part[c];
+#pragma unroll
+        for (int w = 1; w < kRouteBlock / 64; ++w) sum += part[w * len + c];
+        out[c] = sum;
+    }
+    __syncthreads();
+}
+
+// Column sums over the block's tokens of prob[t, c] = exp(a[t,c] - mx_t) * inv_z_t, written to out[c], in a
+// fixed order: a butterfly over the 64 lanes of each wave, then the four wave partials added in wave order.
+// part: LDS [kRouteBlock / 64][len].  Ends with a barrier (part may be reused afterwards).
+__device__ __forceinline__ void block_column_sums(const float *__restrict__ row, const float *__restrict__ bias,
+                                                  int len, float mx, float inv_z, bool valid,
+                                                  float *__restrict__ part, float *__restrict__ out)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int c0 = 0; c0 < len; c0 += kLoadChunk) {
+        float a[kLoadChunk];
+        if (valid) load_biased(row, bias, c0, len, -INFINITY, a);
+#pragma unroll
+        for (int k = 0; k < kLoadChunk; ++k) {
+            if (c0 + k < len) {   // uniform
+                float v = valid ? exp_neg(a[k] - mx) * inv_z : 0.f;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+                if (lane == 0) part[wave * len + c0 + k] = v;
+            }
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < len; c += kRouteBlock) {
+        float sum = part[c];
+#pragma unroll
+        for (int w = 1; w < kRouteBlock / 64; ++w) sum += part[w * len + c];
+        out[c] = sum;
+    }
+    __syncthreads();
+}
+
+// PERWAVE: every wave counts into its own copy of the LDS histograms and the copies are combined after one
+// barrier (needs 4 x (N + n) counters); otherwise the four waves take turns on one copy.
+// CP / CQ: register capacity for the inter / intra logit row (0: rows longer than 32 columns are re-read from
+// memory by every pass).
+template <bool PERWAVE, int CP, int CQ>
 __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     const float *__restrict__ logits_inter, const float *__restrict__ logits_intra,
     const float *__restrict__ bias_inter, const float *__restrict__ bias_intra,
@@ -139,28 +199,40 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     int32_t *__restrict__ block_expert_hist, int32_t *__restrict__ block_group_hist,
     float *__restrict__ block_p_sum, float *__restrict__ block_q_sum)
 {
-    extern __shared__ int32_t hist[];                  // [N] expert counters, then [n] group counters
-    __shared__ float tile[kRouteBlock][kColChunk + 1];
-    __shared__ float part[8][kColChunk];
+    // [N] expert counters then [n] group counters (PERWAVE: one such set per wave); reused afterwards as the
+    // [4][max(n, m)] partial probability sums (both fit: n, m <= N + n)
+    extern __shared__ int32_t hist[];
+    constexpr int kWaves = kRouteBlock / 64;
 
-    const int N = n * m;
-    int32_t *ghist = hist + N;
+    const int N = n * m, NC = N + n;
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int t = b * kRouteBlock + tid;
     const bool valid = t < T;
 
-    for (int i = tid; i < N + n; i += kRouteBlock) hist[i] = 0;
+    for (int i = tid; i < (PERWAVE ? kWaves : 1) * NC; i += kRouteBlock) hist[i] = 0;
 
     int g = 0, l = 0;
     float mx_p = 0.f, iz_p = 0.f, mx_q = 0.f, iz_q = 0.f;
     const float *rp = logits_inter + (size_t)(valid ? t : 0) * n;
     const float *rq = logits_intra + (size_t)(valid ? t : 0) * m;
     const float *bq = nullptr;
+    float ap[CP > 0 ? CP : 1], aq[CQ > 0 ? CQ : 1];
     if (valid) {
-        top1_softmax(rp, bias_inter, n, g, mx_p, iz_p);
+        // the intra row does not depend on the chosen group (only its bias row does): fetch both rows at once
+        if constexpr (CP > 0) load_row<CP>(rp, bias_inter, n, ap);
+        if constexpr (CQ > 0) {
+            if (!bias_intra) load_row<CQ>(rq, nullptr, m, aq);
+        }
+        if constexpr (CP > 0) top1_softmax_row<CP>(ap, g, mx_p, iz_p);
+        else top1_softmax(rp, bias_inter, n, g, mx_p, iz_p);
         bq = bias_intra ? bias_intra + (size_t)g * m : nullptr;
-        top1_softmax(rq, bq, m, l, mx_q, iz_q);
+        if constexpr (CQ > 0) {
+            if (bias_intra) load_row<CQ>(rq, bq, m, aq);
+            top1_softmax_row<CQ>(aq, l, mx_q, iz_q);
+        } else {
+            top1_softmax(rq, bq, m, l, mx_q, iz_q);
+        }
         group_idx[t] = g;
         local_idx[t] = l;
         p_top[t] = iz_p;
@@ -169,36 +241,77 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     }
     __syncthreads();   // counters are zero
 
-    // rank among earlier tokens of this block: the waves take turns in token order
+    // rank among earlier tokens of this block with the same expert / the same group
     const int e = g * m + l;
     const unsigned long long me = match_any(e, bits_N, valid);
     const unsigned long long mg = match_any(g, bits_n, valid);
     const unsigned long long lt = lanemask_lt();
     const int lane = __lane_id();
     const int wave = tid >> 6;
-    for (int w = 0; w < kRouteBlock / 64; ++w) {
-        if (wave == w && valid) {
-            const int base_e = hist[e];
-            const int base_g = ghist[g];
-            rank_in_block[t] = base_e + __popcll(me & lt);
-            pos_in_block[t] = base_g + __popcll(mg & lt);
-            // the last lane of each matching set publishes the new count
-            if (63 - __clzll(me) == lane) hist[e] = base_e + __popcll(me);
-            if (63 - __clzll(mg) == lane) ghist[g] = base_g + __popcll(mg);
+    if constexpr (PERWAVE) {
+        int32_t *mine = hist + wave * NC;
+        if (valid) {   // the last lane of each matching set publishes the wave's count
+            if (63 - __clzll(me) == lane) mine[e] = __popcll(me);
+            if (63 - __clzll(mg) == lane) mine[N + g] = __popcll(mg);
         }
         __syncthreads();
+        if (valid) {
+            int base_e = 0, base_g = 0;
+            for (int w = 0; w < wave; ++w) {
+                base_e += hist[w * NC + e];
+                base_g += hist[w * NC + N + g];
+            }
+            rank_in_block[t] = base_e + __popcll(me & lt);
+            pos_in_block[t] = base_g + __popcll(mg & lt);
+        }
+        for (int i = tid; i < N; i += kRouteBlock) {
+            int c = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) c += hist[w * NC + i];
+            block_expert_hist[(size_t)b * N + i] = c;
+        }
+        for (int i = tid; i < n; i += kRouteBlock) {
+            int c = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) c += hist[w * NC + N + i];
+            block_group_hist[(size_t)b * n + i] = c;
+        }
+        // per-block counts by local index (summed over groups), stored behind the [B][n] group histograms
+        for (int j = tid; j < m; j += kRouteBlock) {
+            int c = 0;
+            for (int i = 0; i < n; ++i)
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) c += hist[w * NC + i * m + j];
+            block_group_hist[(size_t)gridDim.x * n + (size_t)b * m + j] = c;
+        }
+    } else {
+        int32_t *ghist = hist + N;
+        for (int w = 0; w < kWaves; ++w) {   // the waves take turns in token order
+            if (wave == w && valid) {
+                const int base_e = hist[e];
+                const int base_g = ghist[g];
+                rank_in_block[t] = base_e + __popcll(me & lt);
+                pos_in_block[t] = base_g + __popcll(mg & lt);
+                if (63 - __clzll(me) == lane) hist[e] = base_e + __popcll(me);
+                if (63 - __clzll(mg) == lane) ghist[g] = base_g + __popcll(mg);
+            }
+            __syncthreads();
+        }
+        for (int i = tid; i < N; i += kRouteBlock) block_expert_hist[(size_t)b * N + i] = hist[i];
+        for (int i = tid; i < n; i += kRouteBlock) block_group_hist[(size_t)b * n + i] = ghist[i];
+        for (int j = tid; j < m; j += kRouteBlock) {
+            int c = 0;
+            for (int i = 0; i < n; ++i) c += hist[i * m + j];
+            block_group_hist[(size_t)gridDim.x * n + (size_t)b * m + j] = c;
+        }
     }
-    for (int i = tid; i < N; i += kRouteBlock) block_expert_hist[(size_t)b * N + i] = hist[i];
-    for (int i = tid; i < n; i += kRouteBlock) block_group_hist[(size_t)b * n + i] = ghist[i];
-    // per-block counts by local index (summed over groups), stored behind the [B][n] group histograms
-    for (int j = tid; j < m; j += kRouteBlock) {
-        int c = 0;
-        for (int i = 0; i < n; ++i) c += hist[i * m + j];
-        block_group_hist[(size_t)gridDim.x * n + (size_t)b * m + j] = c;
-    }
+    __syncthreads();   // the counters have been read: the memory becomes the partial-sum buffer
 
-    block_column_sums(rp, bias_inter, n, mx_p, iz_p, valid, tile, part, block_p_sum + (size_t)b * n);
-    block_column_sums(rq, bq, m, mx_q, iz_q, valid, tile, part, block_q_sum + (size_t)b * m);
+    float *part = reinterpret_cast<float *>(hist);
+    if constexpr (CP > 0) block_column_sums_row<CP>(ap, n, mx_p, iz_p, valid, part, block_p_sum + (size_t)b * n);
+    else block_column_sums(rp, bias_inter, n, mx_p, iz_p, valid, part, block_p_sum + (size_t)b * n);
+    if constexpr (CQ > 0) block_column_sums_row<CQ>(aq, m, mx_q, iz_q, valid, part, block_q_sum + (size_t)b * m);
+    else block_column_sums(rq, bq, m, mx_q, iz_q, valid, part, block_q_sum + (size_t)b * m);
 }
 
 // Exclusive scan along the block axis of one histogram column (64 blocks per step, one per lane,
@@ -352,11 +465,24 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
 {
     const int n = d.n_groups, m = d.m_local, N = n * m;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
-    const size_t lds1 = sizeof(int32_t) * (size_t)(N + n);
-    hipLaunchKernelGGL(route_decide_kernel, dim3(B), dim3(kRouteBlock), lds1, s, logits_inter, logits_intra,
-                       bias_inter, bias_intra, d.T, n, m, ceil_log2(n), ceil_log2(N), group_idx, local_idx,
-                       ws.pos_in_block, ws.rank_in_block, gate, p_top, q_top, ws.block_expert_hist,
-                       ws.block_group_hist, ws.block_p_sum, ws.block_q_sum);
+    // one histogram copy per wave while four of them fit in 48 KB of LDS (N + n <= 3072)
+    const bool per_wave = (size_t)(N + n) * (kRouteBlock / 64) * sizeof(int32_t) <= 48 * 1024;
+    // the counters' memory is reused for the [4][max(n, m)] partial probability sums
+    const size_t counters = (size_t)(N + n) * (per_wave ? kRouteBlock / 64 : 1);
+    const size_t lds1 = sizeof(int32_t) * std::max(counters, (size_t)(kRouteBlock / 64) * std::max(n, m));
+    const int cp = n <= 8 ? 8 : (n <= 32 ? 32 : 0), cq = m <= 8 ? 8 : (m <= 32 ? 32 : 0);
+#define SMILE_DECIDE(PW, CP, CQ)                                                                                     \
+    hipLaunchKernelGGL((route_decide_kernel<PW, CP, CQ>), dim3(B), dim3(kRouteBlock), lds1, s, logits_inter,          \
+                       logits_intra, bias_inter, bias_intra, d.T, n, m, ceil_log2(n), ceil_log2(N), group_idx,        \
+                       local_idx, ws.pos_in_block, ws.rank_in_block, gate, p_top, q_top, ws.block_expert_hist,         \
+                       ws.block_group_hist, ws.block_p_sum, ws.block_q_sum)
+    if (!per_wave) SMILE_DECIDE(false, 0, 0);
+    else if (cp == 8 && cq == 8) SMILE_DECIDE(true, 8, 8);
+    else if (cp == 32 && cq == 8) SMILE_DECIDE(true, 32, 8);
+    else if (cp == 8 && cq == 32) SMILE_DECIDE(true, 8, 32);
+    else if (cp == 32 && cq == 32) SMILE_DECIDE(true, 32, 32);
+    else SMILE_DECIDE(true, 0, 0);
+#undef SMILE_DECIDE
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !scan) return err;   // !scan: the caller's last step scans the histograms itself
     const int columns = N + 2 * n + 2 * m;
