@@ -1,6 +1,7 @@
 /*
- * libsmile: forward pass of one SMILE bi-level routed Mixture-of-Experts layer
- * on one AMD MI355X (gfx950), as a C-ABI library of hand-written HIP kernels.
+ * libsmile: forward and backward pass of one SMILE bi-level routed
+ * Mixture-of-Experts layer on one AMD MI355X (gfx950), as a C-ABI library of
+ * hand-written HIP kernels.
  *
  * Method: "SMILE: Scaling Mixture-of-Experts with Efficient Bi-level Routing",
  * arXiv 2212.05191.  A token is routed to one of n groups by an inter router
@@ -30,8 +31,8 @@
  *   - Limits: T, d, F, n, m, C >= 1; d % 8 == 0 and F % 8 == 0 (for the 16-bit
  *     types: d % 64 == 0 and F % 64 == 0); n <= 1024, m <= 1024, N <= 4096;
  *     N*C*max(d,F) < 2^40 elements; N*C and T below 2^31 (T <= 2^30 with a
- *     group capacity).  n = 1 (or m = 1)
- *     gives the flat one-level top-1 router of Section 2 (Eq. 1-2, k = 1).
+ *     group capacity).  n = 1 (or m = 1) gives the flat one-level top-1
+ *     router of Section 2 (Eq. 1-2, k = 1).
  *   - Floating-point inputs must be finite; NaN/Inf give unspecified results.
  */
 #ifndef SMILE_H
@@ -235,7 +236,8 @@ typedef struct smile_layer_io {
  *   - io->xe == io->ye == NULL: the permutations are fused into the expert GEMMs --
  *     the up-projection gathers its rows from x through a slot -> token map and the
  *     down-projection returns gate-weighted rows straight to y; rows of dropped
- *     tokens are zeroed by the routing (6 launches, no [N,C,d] traffic). */
+ *     tokens are zeroed by the routing (6 launches, 5 for batches of at most
+ *     16384 tokens; no [N,C,d] traffic). */
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream);
 
 /* ---------------------------------------------------------------------------
@@ -252,9 +254,10 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
  * ------------------------------------------------------------------------- */
 
 /* Bytes of device scratch memory smile_expert_ffn_backward, smile_gate_weights_backward and
- * smile_layer_backward need (recomputed activations, transposed operands, partial sums; about
- * 5 N*C*F + 2 N*C*d + N*d*F elements).  Host-only.  The memory is the caller's, 256-byte aligned,
- * and only used during the call's enqueued work. */
+ * smile_layer_backward need: the recomputed h and pre, the gradient at the pre-activation (3 N*C*F
+ * elements), partial sums of the router-weight gradient, and for fp32 also transposed copies of the
+ * GEMM operands (about 2 N*C*F + 2 N*C*d + N*d*F more).  Host-only.  The memory is the caller's,
+ * 256-byte aligned, and only used during the call's enqueued work. */
 smile_status smile_backward_workspace_bytes(const smile_layer_desc *desc, size_t *bytes);
 
 /* Eq. 3 backwards: for a kept token dye[e, slot[t], :] = gate[t] * dy[t, :] and
