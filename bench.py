@@ -262,7 +262,7 @@ def main():
                                f"capacity={cfg.capacity} (cf {cfg.capacity_factor}) {cfg.dtype} {cfg.act}",
                    "kept_tokens": kept, "dropped_tokens": dropped,
                    "max_over_mean_expert_load": round(float(ecnt.max() / max(ecnt.mean(), 1e-9)), 3)},
-        "roofline": {"kernel": "grouped_gemm_nt_bf16_kernel (expert FFN up-projection + GELU)",
+        "roofline": {"kernel": "grouped_gemm_nt_kernel (expert FFN up-projection + GELU)",
                      "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_us": round(dom_ms * 1e3, 2),

@@ -8,8 +8,8 @@
 // (8 consecutive k per lane), so tiles go global -> LDS -> registers as 16-byte pieces with no
 // transposition anywhere.
 //
-// bf16 kernel (the hot kernel of the layer).  One workgroup computes a BM x BN tile of one expert
-// with v_mfma_f32_32x32x16_bf16 and fp32 accumulators.
+// 16-bit kernel (bf16 or fp16 storage; the hot kernel of the layer).  One workgroup computes a BM x BN tile
+// of one expert with v_mfma_f32_32x32x16_bf16 / _f16 and fp32 accumulators.
 //   * K is cut into slabs of BK elements.  A slab travels global -> LDS directly
 //     (global_load_lds_dwordx4: no staging registers, no ds_write) into a ring of STAGES buffers
 //     with STAGES-1 slabs in flight.  Per slab: wait until this wave's part has landed (s_waitcnt
@@ -21,7 +21,7 @@
 //     32 rows a wave reads for one MFMA operand fall on distinct banks.
 //   * The weight tile is the MFMA "A" operand and the token tile the "B" operand, so a lane ends up
 //     with 4 consecutive output columns of one token row.  The epilogue (bias, activation, round
-//     to bf16) writes them to LDS and the workgroup then stores whole rows, 16 bytes per lane, so
+//     to the storage type) writes them to LDS and the workgroup then stores whole rows, 16 bytes per lane, so
 //     every global store instruction covers full cache lines.
 //   * Traffic L2 -> LDS per flop falls as 1/BM + 1/BN; that path (about 64 B/clk per CU at best)
 //     and not HBM is what bounds small tiles, so tiles are as large as the workload can still
@@ -52,7 +52,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int kXcds = 8;
 
-// ACT: 0 none, 1 ReLU, 2 GELU (erff; fp32 path), 3 GELU (rational erfc; bf16 path)
+// ACT: 0 none, 1 ReLU, 2 GELU (erff; fp32 path), 3 GELU (rational erfc; 16-bit path)
 template <int ACT>
 __device__ __forceinline__ float activate(float v)
 {
@@ -93,7 +93,7 @@ __device__ __forceinline__ float activate_grad(float v)
     }
 }
 
-// ------------------------------------------------------------------------------------ bf16 / MFMA
+// ------------------------------------------------------------------------------------ bf16 / fp16: MFMA
 
 struct GemmArgs {
     const void *x;          // [N][C][K]; with x_rows: the token matrix [T][K]
@@ -150,7 +150,7 @@ __device__ __forceinline__ int swz(int row)
 // E: the 16-bit storage type (__bf16 or _Float16).
 template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT,
           bool DUAL = false, int POST = 0>
-__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_bf16_kernel(GemmArgs a)
+__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(GemmArgs a)
 {
     typedef typename Half<E>::vec8 bf16x8;                                  // one MFMA operand: 8 elements
     typedef __attribute__((__vector_size__(4 * sizeof(E)))) E bf16x4;       // 4 rounded outputs
@@ -370,23 +370,23 @@ void launch_timed(Kernel k, dim3 grid, dim3 block, hipStream_t s, hipEvent_t t0,
 }
 
 template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
-hipError_t launch_bf16_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
+hipError_t launch_half_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(WGM * WGN * 64);
-    if (act == 0) launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
-    else if (act == 1) launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
-    else launch_timed(grouped_gemm_nt_bf16_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
+    if (act == 0) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
+    else if (act == 1) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
+    else launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
     return hipGetLastError();
 }
 
 // The two epilogue variants of the backward pass, on the up-projection tile shape only:
 //   a.y2 given: act(product) and the bare product in one launch;   post != 0: output times act'(a.aux).
 template <typename E>
-hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t s)
+hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, hipStream_t s)
 {
     constexpr int BM = 128, BN = 192;
     a.row_tiles = (a.C + BM - 1) / BM;
@@ -395,12 +395,12 @@ hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid(per_xcd * kXcds), block(256);
     if (a.y2) {
-        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
+        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
     } else if (post == 1) {
-        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((grouped_gemm_nt_bf16_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }
@@ -415,17 +415,17 @@ hipError_t launch_bf16_special(GemmArgs a, int N, int act, int post, hipStream_t
 //     of 128x256 (fewer weight bytes through L2 per flop).
 // Larger tiles (256x128 .. 256x256) move fewer bytes L2 -> LDS per flop but were never faster here.
 template <typename E>
-hipError_t launch_bf16(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
+hipError_t launch_half_typed(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
                        hipEvent_t t1 = nullptr)
 {
     switch (tile) {
-    case 0: return launch_bf16_tile<E, 128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 1: return launch_bf16_tile<E, 128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
-    case 2: return launch_bf16_tile<E, 128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
-    case 3: return launch_bf16_tile<E, 256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
-    case 4: return launch_bf16_tile<E, 128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
-    case 5: return launch_bf16_tile<E, 64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 6: return launch_bf16_tile<E, 256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 0: return launch_half_tile<E, 128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 1: return launch_half_tile<E, 128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
+    case 2: return launch_half_tile<E, 128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
+    case 3: return launch_half_tile<E, 256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
+    case 4: return launch_half_tile<E, 128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 5: return launch_half_tile<E, 64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
+    case 6: return launch_half_tile<E, 256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
     default: return hipErrorInvalidValue;
     }
 }
@@ -544,14 +544,14 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 hipError_t launch_half(int dtype, const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
                        hipEvent_t t1 = nullptr)
 {
-    if (dtype == SMILE_DTYPE_BF16) return launch_bf16<__bf16>(a, N, act, tile, s, t0, t1);
-    return launch_bf16<_Float16>(a, N, act, tile, s, t0, t1);
+    if (dtype == SMILE_DTYPE_BF16) return launch_half_typed<__bf16>(a, N, act, tile, s, t0, t1);
+    return launch_half_typed<_Float16>(a, N, act, tile, s, t0, t1);
 }
 
 hipError_t launch_half_special(int dtype, const GemmArgs &a, int N, int act, int post, hipStream_t s)
 {
-    if (dtype == SMILE_DTYPE_BF16) return launch_bf16_special<__bf16>(a, N, act, post, s);
-    return launch_bf16_special<_Float16>(a, N, act, post, s);
+    if (dtype == SMILE_DTYPE_BF16) return launch_half_special_typed<__bf16>(a, N, act, post, s);
+    return launch_half_special_typed<_Float16>(a, N, act, post, s);
 }
 
 }  // namespace

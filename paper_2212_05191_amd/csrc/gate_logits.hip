@@ -4,8 +4,8 @@
 // one-level router the paper compares against), so the kernel is
 // bound by the single read of x from HBM; the weights (<= 80 KB) stay in L2.
 //
-// bf16: one workgroup of 4 waves owns RT x 16 token rows; the waves split the K (d) range in
-// 64-wide chunks, each feeding v_mfma_f32_16x16x32_bf16 straight from global memory (a lane reads
+// bf16 / fp16: one workgroup of 4 waves owns RT x 16 token rows; the waves split the K (d) range in
+// 64-wide chunks, each feeding v_mfma_f32_16x16x32_bf16 (or _f16) straight from global memory (a lane reads
 // 32 contiguous bytes of its row, so 4 lanes cover a full 128-byte line), then the 4 partial
 // accumulators are summed through LDS in a fixed order.  Every workgroup re-reads the router
 // weights from L2, so RT grows with T (weight traffic / RT) while keeping >= 512 workgroups:
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void gate_logits_f32_kernel(
 }
 
 template <int CT, int RT>
-void launch_bf16_rt(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+void launch_half_rt(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
                     float *logits_inter, float *logits_intra, int col0, hipStream_t s)
 {
     const int blocks = (d.T + kRows * RT - 1) / (kRows * RT);
@@ -145,13 +145,13 @@ void launch_bf16_rt(const smile_layer_desc &d, const void *x, const void *w_inte
 
 // columns [col0, col0 + 16*CT)
 template <int CT>
-void launch_bf16(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
+void launch_half(const smile_layer_desc &d, const void *x, const void *w_inter, const void *w_intra,
                  float *logits_inter, float *logits_intra, int col0, hipStream_t s)
 {
     // the accumulators of RT x CT tiles must stay in registers: RT * CT <= 16
-    if (d.T >= 32768 && CT <= 4) launch_bf16_rt<CT, 4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
-    else if (d.T >= 16384) launch_bf16_rt<CT, 2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
-    else launch_bf16_rt<CT, 1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
+    if (d.T >= 32768 && CT <= 4) launch_half_rt<CT, 4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
+    else if (d.T >= 16384) launch_half_rt<CT, 2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
+    else launch_half_rt<CT, 1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s);
 }
 
 }  // namespace
@@ -165,14 +165,14 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
         // router over all N experts) take several passes
         for (int col0 = 0; col0 < cols; col0 += 128) {
             switch ((std::min(cols - col0, 128) + 15) / 16) {
-            case 1: launch_bf16<1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 2: launch_bf16<2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 3: launch_bf16<3>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 4: launch_bf16<4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 5: launch_bf16<5>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 6: launch_bf16<6>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            case 7: launch_bf16<7>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
-            default: launch_bf16<8>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 1: launch_half<1>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 2: launch_half<2>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 3: launch_half<3>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 4: launch_half<4>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 5: launch_half<5>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 6: launch_half<6>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            case 7: launch_half<7>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
+            default: launch_half<8>(d, x, w_inter, w_intra, logits_inter, logits_intra, col0, s); break;
             }
         }
     } else {

@@ -116,7 +116,7 @@ struct OperandTile {
 };
 
 template <typename E, int BM, int BN, int WGM, int WGN, int STAGES, int OCC, bool XT, bool WT, int POST>
-__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_bf16_kernel(TGemmArgs<E> a)
+__global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGemmArgs<E> a)
 {
     typedef typename Half<E>::vec8 bf16x8;                              // one MFMA operand: 8 elements
     typedef __attribute__((__vector_size__(4 * sizeof(E)))) E bf16x4;   // 4 rounded outputs
@@ -365,7 +365,7 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL((grouped_gemm_t_bf16_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
+    hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
                        dim3(256), 0, s, a);
     return hipGetLastError();
 }
