@@ -229,18 +229,29 @@ __global__ __launch_bounds__(kThreads) void dispatch_backward_kernel(
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[k] = 0.f;
         }
-        for (int i = 0; i < n; ++i) {
-            const float g = lp[i];
-            Piece<DT>::unpack(w_inter[(size_t)i * ppr + c], w);
+        // acc += sum_i dl[i] * rows[i][c], eight rows at a time with all their loads issued first
+        auto add_rows = [&](const u32x4 *__restrict__ rows, const float *__restrict__ dl, int count) {
+            for (int i0 = 0; i0 < count; i0 += 8) {
+                u32x4 wp[8];
+                float g[8];
 #pragma unroll
-            for (int k = 0; k < E; ++k) acc[k] = fmaf(g, w[k], acc[k]);
-        }
-        for (int j = 0; j < m; ++j) {
-            const float g = lq[j];
-            Piece<DT>::unpack(w_intra[(size_t)j * ppr + c], w);
+                for (int q = 0; q < 8; ++q) {
+                    const int i = min(i0 + q, count - 1);
+                    wp[q] = rows[(size_t)i * ppr + c];
+                    g[q] = dl[i];
+                }
 #pragma unroll
-            for (int k = 0; k < E; ++k) acc[k] = fmaf(g, w[k], acc[k]);
-        }
+                for (int q = 0; q < 8; ++q) {
+                    if (i0 + q < count) {
+                        Piece<DT>::unpack(wp[q], w);
+#pragma unroll
+                        for (int k = 0; k < E; ++k) acc[k] = fmaf(g[q], w[k], acc[k]);
+                    }
+                }
+            }
+        };
+        add_rows(w_inter, lp, n);
+        add_rows(w_intra, lq, m);
         dx[(size_t)t * ppr + c] = Piece<DT>::pack(acc);
     }
 }
