@@ -4,7 +4,8 @@
 //   route_decide   one thread per token: biased logits (both rows fetched at once and kept in registers
 //                  for routers of up to 32 columns) -> top-1 group and local expert, the two softmax
 //                  probabilities (Eq. 1 read as a softmax), the gate p*q (Eq. 3); per-block column sums
-//                  of p and q (wave butterflies, then the waves in order); the token's rank among
+//                  of p and q in a fixed order (wave butterflies for routers of up to 8 columns, an
+//                  LDS tile summed in segments otherwise); the token's rank among
 //                  EARLIER tokens of the same block with the same group / the same expert (wave64
 //                  ballots + per-wave LDS counters combined after one barrier); per-block histograms.
 //   route_scan     one wave per histogram column: exclusive scan along the block axis (turning the
@@ -153,35 +154,41 @@ __device__ __forceinline__ void block_column_sums_row(const float (&a)[CAP], int
     __syncthreads();
 }
 
-// Column sums over the block's tokens of prob[t, c] = exp(a[t,c] - mx_t) * inv_z_t, written to out[c], in a
-// fixed order: a butterfly over the 64 lanes of each wave, then the four wave partials added in wave order.
-// part: LDS [kRouteBlock / 64][len].  Ends with a barrier (part may be reused afterwards).
-__device__ __forceinline__ void block_column_sums(const float *__restrict__ row, const float *__restrict__ bias,
-                                                  int len, float mx, float inv_z, bool valid,
-                                                  float *__restrict__ part, float *__restrict__ out)
+constexpr int kColChunk = 32;   // probability columns summed per LDS pass
+
+// Column sums over the block's tokens of prob[t, c] = exp(a[t,c] - mx_t) * inv_z_t, written to out[c], for
+// routers of more than 8 columns: the probabilities go through an LDS tile, 32 columns at a time, and are summed
+// in a fixed order (8 segments of 32 tokens serially, then the 8 partials serially).  GET(c) yields the biased
+// logit of column c (from registers or from memory).
+template <typename Get>
+__device__ __forceinline__ void block_column_sums_tile(Get get, int len, float mx, float inv_z, bool valid,
+                                                       float (*tile)[kColChunk + 1], float (*part)[kColChunk],
+                                                       float *__restrict__ out)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int c0 = 0; c0 < len; c0 += kLoadChunk) {
-        float a[kLoadChunk];
-        if (valid) load_biased(row, bias, c0, len, -INFINITY, a);
-#pragma unroll
-        for (int k = 0; k < kLoadChunk; ++k) {
-            if (c0 + k < len) {   // uniform
-                float v = valid ? exp_neg(a[k] - mx) * inv_z : 0.f;
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-                if (lane == 0) part[wave * len + c0 + k] = v;
-            }
+    const int tid = threadIdx.x;
+    for (int c0 = 0; c0 < len; c0 += kColChunk) {
+        const int w = min(kColChunk, len - c0);
+        get(c0, w, tile[tid]);   // tile[tid][k] = biased logit of column c0 + k for k < w (valid threads only)
+        if (valid) {
+            for (int k = 0; k < w; ++k) tile[tid][k] = exp_neg(tile[tid][k] - mx) * inv_z;
+        } else {
+            for (int k = 0; k < w; ++k) tile[tid][k] = 0.f;
         }
+        __syncthreads();
+        const int col = tid & (kColChunk - 1), seg = tid / kColChunk;   // 8 segments of 32 tokens
+        if (col < w) {
+            float s = 0.f;
+            for (int j = 0; j < kRouteBlock / 8; ++j) s += tile[seg * (kRouteBlock / 8) + j][col];
+            part[seg][col] = s;
+        }
+        __syncthreads();
+        if (tid < w) {
+            float s = 0.f;
+            for (int sg = 0; sg < 8; ++sg) s += part[sg][tid];
+            out[c0 + tid] = s;
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int c = tid; c < len; c += kRouteBlock) {
-        float sum = part[c];
-#pragma unroll
-        for (int w = 1; w < kRouteBlock / 64; ++w) sum += part[w * len + c];
-        out[c] = sum;
-    }
-    __syncthreads();
 }
 
 // PERWAVE: every wave counts into its own copy of the LDS histograms and the copies are combined after one
@@ -202,6 +209,8 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     // [N] expert counters then [n] group counters (PERWAVE: one such set per wave); reused afterwards as the
     // [4][max(n, m)] partial probability sums (both fit: n, m <= N + n)
     extern __shared__ int32_t hist[];
+    __shared__ float tile[kRouteBlock][kColChunk + 1];
+    __shared__ float part8[8][kColChunk];
     constexpr int kWaves = kRouteBlock / 64;
 
     const int N = n * m, NC = N + n;
@@ -307,11 +316,49 @@ __global__ __launch_bounds__(kRouteBlock) void route_decide_kernel(
     }
     __syncthreads();   // the counters have been read: the memory becomes the partial-sum buffer
 
+    // per-block column sums of p and q: wave butterflies for routers of at most 8 columns (registers), else
+    // through the LDS tile
     float *part = reinterpret_cast<float *>(hist);
-    if constexpr (CP > 0) block_column_sums_row<CP>(ap, n, mx_p, iz_p, valid, part, block_p_sum + (size_t)b * n);
-    else block_column_sums(rp, bias_inter, n, mx_p, iz_p, valid, part, block_p_sum + (size_t)b * n);
-    if constexpr (CQ > 0) block_column_sums_row<CQ>(aq, m, mx_q, iz_q, valid, part, block_q_sum + (size_t)b * m);
-    else block_column_sums(rq, bq, m, mx_q, iz_q, valid, part, block_q_sum + (size_t)b * m);
+    if constexpr (CP == 8) {
+        block_column_sums_row<CP>(ap, n, mx_p, iz_p, valid, part, block_p_sum + (size_t)b * n);
+    } else if constexpr (CP > 0) {
+        block_column_sums_tile([&](int c0, int w, float *dst) {
+#pragma unroll
+            for (int k = 0; k < CP; ++k)
+                if (k >= c0 && k < c0 + w) dst[k - c0] = ap[k];
+        }, n, mx_p, iz_p, valid, tile, part8, block_p_sum + (size_t)b * n);
+    } else {
+        block_column_sums_tile([&](int c0, int w, float *dst) {
+            if (!valid) return;
+            for (int i0 = 0; i0 < w; i0 += kLoadChunk) {
+                float a[kLoadChunk];
+                load_biased(rp, bias_inter, c0 + i0, n, -INFINITY, a);
+#pragma unroll
+                for (int k = 0; k < kLoadChunk; ++k)
+                    if (i0 + k < w) dst[i0 + k] = a[k];
+            }
+        }, n, mx_p, iz_p, valid, tile, part8, block_p_sum + (size_t)b * n);
+    }
+    if constexpr (CQ == 8) {
+        block_column_sums_row<CQ>(aq, m, mx_q, iz_q, valid, part, block_q_sum + (size_t)b * m);
+    } else if constexpr (CQ > 0) {
+        block_column_sums_tile([&](int c0, int w, float *dst) {
+#pragma unroll
+            for (int k = 0; k < CQ; ++k)
+                if (k >= c0 && k < c0 + w) dst[k - c0] = aq[k];
+        }, m, mx_q, iz_q, valid, tile, part8, block_q_sum + (size_t)b * m);
+    } else {
+        block_column_sums_tile([&](int c0, int w, float *dst) {
+            if (!valid) return;
+            for (int i0 = 0; i0 < w; i0 += kLoadChunk) {
+                float a[kLoadChunk];
+                load_biased(rq, bq, c0 + i0, m, -INFINITY, a);
+#pragma unroll
+                for (int k = 0; k < kLoadChunk; ++k)
+                    if (i0 + k < w) dst[i0 + k] = a[k];
+            }
+        }, m, mx_q, iz_q, valid, tile, part8, block_q_sum + (size_t)b * m);
+    }
 }
 
 // Exclusive scan along the block axis of one histogram column (64 blocks per step, one per lane,
