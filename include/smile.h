@@ -232,7 +232,8 @@ typedef struct smile_layer_io {
  * and bit-identical results as calling them one by one, with fewer launches:
  *   - io->xe and io->ye given: the expert buffers are materialised as by
  *     smile_dispatch / smile_expert_ffn; the last routing step and the loss run
- *     inside the dispatch kernel (7 launches instead of 9);
+ *     inside the dispatch kernel and the down-projection also writes y (6 launches
+ *     instead of 9);
  *   - io->xe == io->ye == NULL: the permutations are fused into the expert GEMMs --
  *     the up-projection gathers its rows from x through a slot -> token map and the
  *     down-projection returns gate-weighted rows straight to y; rows of dropped

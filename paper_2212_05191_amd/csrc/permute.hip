@@ -87,13 +87,16 @@ __global__ __launch_bounds__(kThreads) void dispatch_hop2_kernel(
 
 // Dispatch fused with the last routing step (the chained forward pass): every thread derives the
 // token's final slot from the workspace (block offset of its expert + rank inside the block,
-// dropped at or beyond C); the thread moving piece 0 of a token also writes slot / pos_in_group.
+// dropped at or beyond C); the thread moving piece 0 of a token also writes slot / pos_in_group and
+// the slot -> token map; the output rows of dropped tokens are zeroed here (the down-projection
+// returns the gate-weighted rows of the kept ones, so no combine kernel follows).
 template <int LPR>
 __global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
     const u32x4 *__restrict__ x, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
     const int32_t *__restrict__ block_expert_off, const int32_t *__restrict__ block_group_off,
     const int32_t *__restrict__ rank_in_block, const int32_t *__restrict__ pos_in_block,
     int32_t *__restrict__ pos_in_group, int32_t *__restrict__ slot, u32x4 *__restrict__ xe,
+    int32_t *__restrict__ slot_token, u32x4 *__restrict__ y,
     int T, int ppr, int n, int m, int C, LossArgs loss, float alpha, float beta)
 {
     // Eq. 4 from the (complete) routing statistics, by the first wave of the last workgroup
@@ -108,8 +111,13 @@ __global__ __launch_bounds__(kThreads) void dispatch_finalize_kernel(
     if (rl.sub == 0) {
         slot[t] = sl;
         pos_in_group[t] = block_group_off[(size_t)b * n + g] + pos_in_block[t];
+        if (sl >= 0) slot_token[(size_t)e * C + sl] = t;   // for the down-projection's gate-weighted return
     }
-    if (sl < 0) return;
+    if (sl < 0) {   // a dropped token's output row is zero (Eq. 3 gives it no expert output)
+        u32x4 *row = y + (size_t)t * ppr;
+        for (int c = rl.sub; c < ppr; c += LPR) row[c] = u32x4{0u, 0u, 0u, 0u};
+        return;
+    }
     move_row<LPR>(x + (size_t)t * ppr, xe + ((size_t)e * C + sl) * ppr, ppr, rl.sub, [](u32x4 v) { return v; });
 }
 
@@ -340,7 +348,7 @@ hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const
 
 hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
-                                    int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s)
+                                    int32_t *slot, void *xe, void *y, const LossArgs &loss, hipStream_t s)
 {
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
@@ -348,8 +356,8 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
     SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_finalize_kernel<L>, grid, block, 0, s,
                                              static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist,
                                              ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group, slot,
-                                             static_cast<u32x4 *>(xe), d.T, ppr, d.n_groups, d.m_local, d.capacity, loss,
-                                             d.alpha, d.beta));
+                                             static_cast<u32x4 *>(xe), ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr,
+                                             d.n_groups, d.m_local, d.capacity, loss, d.alpha, d.beta));
     return hipGetLastError();
 }
 

@@ -285,7 +285,8 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
     if (bad_opt(io->h_save) || bad_opt(io->pre_save) || (io->h_save == nullptr) != (io->pre_save == nullptr))
         return SMILE_INVALID_ARG;
     // Same kernels as the step-by-step calls with fewer launches.  With expert buffers (xe, ye given):
-    // the last routing step and the loss run inside the dispatch kernel.  Without them (both NULL):
+    // the last routing step and the loss run inside the dispatch kernel, and the down-projection also
+    // returns the gate-weighted rows to y (no combine launch).  Without them (both NULL):
     // nothing is materialised -- a per-token kernel finishes the routing, builds the slot -> token map
     // and zeroes the rows of dropped tokens; the up GEMM gathers its rows from x through that map and
     // the down GEMM returns gate-weighted rows straight to y.
@@ -321,16 +322,15 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
     }
     if (err == hipSuccess)
         err = launch_dispatch_finalize(d, ctx->ws, io->x, io->group_idx, io->local_idx, io->pos_in_group, io->slot,
-                                       io->xe, loss, s);
+                                       io->xe, io->y, loss, s);
     if (err == hipSuccess)
         err = launch_expert_ffn_up(d, ctx->ws, io->xe, io->kept_count, io->w1, io->b1, s,
                                    static_cast<hipEvent_t>(io->prof_up_start), static_cast<hipEvent_t>(io->prof_up_stop),
                                    nullptr, io->h_save, io->pre_save);
+    // the down-projection writes ye and, through the slot -> token map, the gate-weighted rows of y
     if (err == hipSuccess)
-        err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, io->ye, s, nullptr, nullptr,
+        err = launch_expert_ffn_down(d, ctx->ws, io->kept_count, io->w2, io->b2, io->ye, s, io->y, io->gate,
                                      io->h_save);
-    if (err == hipSuccess)
-        err = launch_combine(d, io->ye, io->group_idx, io->local_idx, io->slot, io->gate, io->y, s);
     return from_hip(err);
 }
 

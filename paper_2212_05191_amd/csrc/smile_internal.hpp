@@ -175,11 +175,12 @@ hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const
                                 int group_rows, void *xe, hipStream_t s);
 
 // dispatch fused with the last routing step: computes pos_in_group / slot from the workspace ranks
-// and block offsets, writes them, and moves the rows; loss != nullptr: one wave also evaluates Eq. 4
-// from the routing statistics (saves the separate loss launch)
+// and block offsets, writes them, moves the rows, records the slot -> token map in ws.slot_token and
+// zeroes the rows of dropped tokens in y; loss != nullptr: one wave also evaluates Eq. 4 from the
+// routing statistics (saves the separate loss launch)
 hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &ws, const void *x,
                                     const int32_t *group_idx, const int32_t *local_idx, int32_t *pos_in_group,
-                                    int32_t *slot, void *xe, const LossArgs &loss, hipStream_t s);
+                                    int32_t *slot, void *xe, void *y, const LossArgs &loss, hipStream_t s);
 
 hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32_t *group_idx,
                           const int32_t *local_idx, const int32_t *slot, const float *gate, void *y, hipStream_t s);
