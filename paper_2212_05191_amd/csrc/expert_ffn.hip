@@ -27,11 +27,15 @@
 //     and not HBM is what bounds small tiles, so tiles are as large as the workload can still
 //     spread over 256 CUs.
 //
-// The grid covers every (expert, column tile, row tile); tiles whose first row is >= kept[e] exit
-// at once, so no host synchronisation on the routing result is needed.  Workgroup ids are dealt
-// round-robin to the 8 XCDs by the hardware; the id is remapped so that each XCD (own L2) works
-// on a contiguous range of tiles: the row tiles sharing a weight tile and the column tiles
-// sharing a token tile then meet in the same L2.
+// Plain grid (at most a few tiles per workgroup slot of the chip): it covers every (expert, column tile,
+// row tile); tiles whose first row is >= kept[e] exit at once, so no host synchronisation on the routing
+// result is needed.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id is remapped
+// so that each XCD (own L2) works on a contiguous range of tiles: the row tiles sharing a weight tile and
+// the column tiles sharing a token tile then meet in the same L2.
+// Persistent grid (many tiles per slot): one workgroup per slot walks the live tiles only, in the same
+// order (LiveTileWalk), again without any host knowledge of the row counts.  When experts are far below
+// capacity this is up to 25 % faster: a workgroup of an empty tile still has to wait for a free slot (its
+// LDS) before it can exit, in turn with the live ones.
 //
 // fp32 kernel (small / reference-precision configurations): classic LDS-tiled FMA GEMM.
 #include <cstdlib>
@@ -110,6 +114,7 @@ struct GemmArgs {
     const float *gate;      // [T]
     void *y2 = nullptr;     // [N][C][Nout]: the same product without the activation (DUAL kernels only)
     const void *aux = nullptr;   // [N][C][Nout]: POST kernels multiply the output by act'(aux)
+    int N = 0;                   // experts (PERSIST kernels walk the live row tiles of all of them)
 };
 
 // One 16-byte piece (8 elements) times a gate: fp32 product, rounded to the storage type (nearest even) --
@@ -149,7 +154,7 @@ __device__ __forceinline__ int swz(int row)
 // pre-activation, dh * act'(pre)); aux is read with the same row-contiguous 16-byte accesses as the store.
 // E: the 16-bit storage type (__bf16 or _Float16).
 template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC, int SWZ, int ACT,
-          bool DUAL = false, int POST = 0>
+          bool DUAL = false, int POST = 0, bool PERSIST = false>
 __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(GemmArgs a)
 {
     typedef typename Half<E>::vec8 bf16x8;                                  // one MFMA operand: 8 elements
@@ -172,49 +177,88 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
 
     __shared__ u32x4 lds[STAGES * STAGE];
 
-    // ---- which tile (XCD-aware remap of the hardware's round-robin workgroup placement)
-    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (lid >= a.tiles) return;
-    const int per_expert = a.row_tiles * a.col_tiles;
-    const int e = lid / per_expert;
-    const int rem = lid - e * per_expert;
-    const int ct = rem / a.row_tiles, rt = rem - ct * a.row_tiles;
-    const int rows = a.kept ? min(a.kept[e], a.C) : a.C;   // never trust a count beyond the buffer
-    if (rt * BM >= rows) return;
-
     const int K = a.K, Nout = a.Nout;
-    const E *X = static_cast<const E *>(a.x) + (a.x_rows ? (size_t)0 : (size_t)e * a.C * K);
-    const E *W = static_cast<const E *>(a.w) + (size_t)e * Nout * K;
-    const int32_t *x_rows = a.x_rows ? a.x_rows + (size_t)e * a.C : nullptr;
+    const int slabs = K / BK;
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WGM, wn = wave / WGM;
-
-    // ---- this lane's source address in each of the wave's load instructions
-    const int lr = lane / PPR, lp = lane % PPR;
-    const E *src[GPW];
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-        const int row = (wave + i * NW) * RPI + lr;            // row of the stage
-        const int piece = lp ^ swz<BK, SWZ>(row);
-        // rows past the end of the expert's tokens / of the weight matrix re-read the last valid one
-        if (row < BM) {
-            const int xr = min(rt * BM + row, rows - 1);
-            src[i] = X + (size_t)(x_rows ? x_rows[xr] : xr) * K + piece * 8;
+    // ---- which tile(s).
+    // Plain kernels: one tile per workgroup; the id is remapped so that each XCD gets a contiguous range
+    // (the hardware deals workgroup ids round-robin to the 8 XCDs).
+    // PERSIST kernels: one workgroup per slot of the chip walks the live tiles (LiveTileWalk).  The first
+    // slabs of the next tile are requested before the epilogue of the current one (PREFETCH), which then
+    // stages its output in the one pipeline buffer those loads do not touch.
+    constexpr bool PREFETCH = PERSIST && OROWS * OSTRIDE <= STAGE;
+    constexpr int STG = PREFETCH ? (STAGES - 1) * STAGE : 0;   // staging area, in 16-byte units
+    LiveTileWalk<BM> walk;
+    if constexpr (PERSIST) walk.init(a.kept, a.N, a.C, a.col_tiles);
+    struct Tile {
+        int e, rt, ct, rows;
+    };
+    // the tile of the current ticket (PERSIST) / of this workgroup (plain); false when there is none
+    auto select = [&](Tile &t) {
+        if constexpr (PERSIST) {
+            if (!walk.tile(t.e, t.rt, t.ct)) return false;
         } else {
-            src[i] = W + (size_t)min(ct * BN + row - BM, Nout - 1) * K + piece * 8;
+            const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
+            const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+            if (lid >= a.tiles) return false;
+            const int per_expert = a.row_tiles * a.col_tiles;
+            t.e = lid / per_expert;
+            const int rem = lid - t.e * per_expert;
+            t.ct = rem / a.row_tiles, t.rt = rem - t.ct * a.row_tiles;
         }
-    }
-    auto issue = [&](int slab, int stage) {
+        t.rows = a.kept ? min(a.kept[t.e], a.C) : a.C;   // never trust a count beyond the buffer
+        return t.rt * BM < t.rows;
+    };
+
+    // ---- loads.  src: this lane's source address in each of the wave's load instructions of a slab.
+    const E *src[GPW];
+    auto issue = [&](int wave, int slab, int stage) {
 #pragma unroll
         for (int i = 0; i < GPW; ++i)
             __builtin_amdgcn_global_load_lds(SMILE_GPTR(src[i] + slab * BK),
                                              SMILE_LPTR(&lds[stage * STAGE + (wave + i * NW) * 64]), 16, 0, 0);
     };
+    // Per-lane indices are derived afresh wherever they are needed (PERSIST: through an opaque copy of the
+    // thread id), so that nothing computed from them stays in registers from one tile to the next.
+    auto thread_id = [&]() {
+        int tid = threadIdx.x;
+        if constexpr (PERSIST) asm volatile("" : "+v"(tid));
+        return tid;
+    };
+    // source addresses of a tile and the requests for its first STAGES-1 slabs
+    auto start_tile = [&](const Tile &t) {
+        const int tid = thread_id(), lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int lr = lane / PPR, lp = lane % PPR;
+        const E *X = static_cast<const E *>(a.x) + (a.x_rows ? (size_t)0 : (size_t)t.e * a.C * K);
+        const E *W = static_cast<const E *>(a.w) + (size_t)t.e * Nout * K;
+        const int32_t *x_rows = a.x_rows ? a.x_rows + (size_t)t.e * a.C : nullptr;
+#pragma unroll
+        for (int i = 0; i < GPW; ++i) {
+            const int row = (wave + i * NW) * RPI + lr;            // row of the stage
+            const int piece = lp ^ swz<BK, SWZ>(row);
+            // rows past the end of the expert's tokens / of the weight matrix re-read the last valid one
+            if (row < BM) {
+                const int xr = min(t.rt * BM + row, t.rows - 1);
+                src[i] = X + (size_t)(x_rows ? x_rows[xr] : xr) * K + piece * 8;
+            } else {
+                src[i] = W + (size_t)min(t.ct * BN + row - BM, Nout - 1) * K + piece * 8;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < slabs) issue(wave, s, s);
+    };
 
-    // ---- LDS -> MFMA operands: lane reads row (lane & 31), pieces 2*kk + (lane >> 5)
+    Tile cur;
+    if (!select(cur)) return;
+    start_tile(cur);
+    for (;;) {
+    const int e = cur.e, rt = cur.rt, ct = cur.ct, rows = cur.rows;
+    const int tid = thread_id(), lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    // LDS -> MFMA operands: lane reads row (lane & 31), pieces 2*kk + (lane >> 5)
     const int frow = lane & 31, fhi = lane >> 5, fsw = swz<BK, SWZ>(lane);   // tile bases are multiples of 32
     const int xbase = (wm * WM + frow) * PPR, wbase = (BM + wn * WN + frow) * PPR;
 
@@ -226,11 +270,6 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int slabs = K / BK;
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < slabs) issue(s, s);
-
     int stage = 0;
     const bool wave_live = rt * BM + wm * WM < rows;   // wave-uniform
     // One K slab.  ISSUE: this iteration also issues the loads of slab kt+STAGES-1 (always true in
@@ -241,29 +280,32 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
     auto slab_step = [&](auto issue_tag, int kt) {
         constexpr bool ISSUE = decltype(issue_tag)::value;
         if (ISSUE) {
-            wait_vmcnt<(STAGES - 2) * GPW>();
+            // a prefetched tile's first slabs were requested before the previous tile's stores: wait for all
+            if (PREFETCH && STAGES > 2 && kt == 0) wait_vmcnt<0>();
+            else wait_vmcnt<(STAGES - 2) * GPW>();
         } else {
             const int ahead = slabs - 1 - kt;   // 0 .. STAGES-2 slabs were issued after this one
-            if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
+            if (PREFETCH && kt == 0) wait_vmcnt<0>();
+            else if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
             else if (STAGES >= 3 && ahead == 1) wait_vmcnt<GPW>();
             else wait_vmcnt<0>();
         }
         __builtin_amdgcn_s_barrier();
         const int nstage = stage == 0 ? STAGES - 1 : stage - 1;
         const int nxt = kt + STAGES - 1;
-        const u32x4 *cur = lds + stage * STAGE;
+        const u32x4 *cur_stage = lds + stage * STAGE;
         bf16x8 xf[2][TM], wf[2][TN];
         auto fetch = [&](int buf, int kk) {
             const int p = (2 * kk + fhi) ^ fsw;
 #pragma unroll
-            for (int j = 0; j < TM; ++j) xf[buf][j] = __builtin_bit_cast(bf16x8, cur[xbase + j * 32 * PPR + p]);
+            for (int j = 0; j < TM; ++j) xf[buf][j] = __builtin_bit_cast(bf16x8, cur_stage[xbase + j * 32 * PPR + p]);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, cur[wbase + i * 32 * PPR + p]);
+            for (int i = 0; i < TN; ++i) wf[buf][i] = __builtin_bit_cast(bf16x8, cur_stage[wbase + i * 32 * PPR + p]);
         };
         constexpr int KS = BK / 16;
         if (!wave_live) {
             // none of this wave's token rows exists (ragged tile): it only helps loading
-            if (ISSUE) issue(nxt, nstage);
+            if (ISSUE) issue(wave, nxt, nstage);
             stage = stage + 1 == STAGES ? 0 : stage + 1;
             return;
         }
@@ -302,13 +344,20 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
     for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
     for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
 
+    Tile nxt_tile;
+    bool more = false;
+    if constexpr (PERSIST) {
+        walk.advance();
+        more = select(nxt_tile);
+    }
+
     // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4,
     // row lane%32) of its 32x32 tile.  One pass per 32-row slice of the wave tiles: bias +
     // activation + rounding, 8-byte writes into a [OROWS][BN] staging tile, then row-contiguous
     // 16-byte global stores by the whole workgroup.
     const int32_t *y_rows = a.y_rows ? a.y_rows + (size_t)e * a.C : nullptr;
     const E *bias = a.bias ? static_cast<const E *>(a.bias) + (size_t)e * Nout : nullptr;
-    u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
+    u32x2 *stg = reinterpret_cast<u32x2 *>(lds + STG);
     constexpr int OPR = BN / 8;   // 16-byte pieces per output row
 #pragma unroll
     for (int pass = 0; pass < (DUAL ? 2 : 1); ++pass) {
@@ -318,6 +367,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
         for (int j = 0; j < TM; ++j) {
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
             __builtin_amdgcn_s_barrier();          // main-loop reads / the previous pass's stores are finished
+            if (PREFETCH && pass == 0 && j == 0 && more) start_tile(nxt_tile);
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -340,7 +390,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
                 const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
                 const int col = ct * BN + piece * 8;
                 if (row < rows && col < Nout) {
-                    u32x4 v = lds[orow * OSTRIDE + piece];
+                    u32x4 v = lds[STG + orow * OSTRIDE + piece];
                     if constexpr (POST != 0) {
                         const u32x4 p = *reinterpret_cast<const u32x4 *>(
                             static_cast<const E *>(a.aux) + ((size_t)e * a.C + row) * Nout + col);
@@ -359,6 +409,15 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
             }
         }
     }
+    if (!more) return;
+    if constexpr (!PREFETCH) {
+        // the next tile's first loads overwrite the staging area: every wave must be done reading it
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        start_tile(nxt_tile);
+    }
+    cur = nxt_tile;
+    }   // tile loop
 }
 
 // t0/t1 (both or neither): events that receive the begin / end timestamps of the kernel itself.
@@ -375,8 +434,17 @@ hipError_t launch_half_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
-    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    const dim3 grid(per_xcd * kXcds), block(WGM * WGN * 64);
+    a.N = N;
+    constexpr int slots = workgroup_slots(WGM * WGN, OCC, STAGES * (BM + BN) * BK * 2);
+    const dim3 block(WGM * WGN * 64);
+    if (use_persistent_grid(N, a.tiles, slots)) {
+        const dim3 grid(slots);
+        if (act == 0) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0, false, 0, true>, grid, block, s, t0, t1, a);
+        else if (act == 1) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1, false, 0, true>, grid, block, s, t0, t1, a);
+        else launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3, false, 0, true>, grid, block, s, t0, t1, a);
+        return hipGetLastError();
+    }
+    const dim3 grid((a.tiles + kXcds - 1) / kXcds * kXcds);
     if (act == 0) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0>, grid, block, s, t0, t1, a);
     else if (act == 1) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1>, grid, block, s, t0, t1, a);
     else launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 3>, grid, block, s, t0, t1, a);
@@ -392,15 +460,19 @@ hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, hipSt
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
-    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    const dim3 grid(per_xcd * kXcds), block(256);
+    a.N = N;
+    constexpr int slots = workgroup_slots(4, 2, 2 * (BM + BN) * 64 * 2);
+    const bool persist = use_persistent_grid(N, a.tiles, slots);
+    const dim3 plain((a.tiles + kXcds - 1) / kXcds * kXcds), grid(persist ? dim3(slots) : plain), block(256);
     if (a.y2) {
-        if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+        if (act == 1 && persist) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true, 0, true>), grid, block, 0, s, a);
+        else if (act == 1) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true>), grid, block, 0, s, a);
+        else if (persist) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 3, true, 0, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 3, true>), grid, block, 0, s, a);
     } else if (post == 1) {
-        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 1>), plain, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 0, false, 2>), plain, block, 0, s, a);
     }
     return hipGetLastError();
 }
@@ -560,6 +632,13 @@ hipError_t launch_half_special(int dtype, const GemmArgs &a, int N, int act, int
 }
 
 }  // namespace
+
+bool use_persistent_grid(int N, long long tiles, int slots)
+{
+    if (N > 4096) return false;   // the tile walk keeps one lane per 64 groups
+    if (const char *env = std::getenv("SMILE_FFN_PERSIST")) return std::atoi(env) != 0;
+    return tiles >= 4LL * slots;
+}
 
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s)
 {

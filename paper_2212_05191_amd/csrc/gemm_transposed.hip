@@ -88,6 +88,7 @@ struct TGemmArgs {
     int ldx, ldw;                // leading dimensions (elements) of x and w
     long long sx, sw, sy;        // per-group strides (elements) of x, w and y / aux
     int row_tiles, col_tiles, tiles;
+    int N;                       // groups
 };
 
 // One operand tile of a stage, as seen by the loader and by the MFMA fragment reader.
@@ -115,7 +116,7 @@ struct OperandTile {
     }
 };
 
-template <typename E, int BM, int BN, int WGM, int WGN, int STAGES, int OCC, bool XT, bool WT, int POST>
+template <typename E, int BM, int BN, int WGM, int WGN, int STAGES, int OCC, bool XT, bool WT, int POST, bool PERSIST = false>
 __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGemmArgs<E> a)
 {
     typedef typename Half<E>::vec8 bf16x8;                              // one MFMA operand: 8 elements
@@ -136,23 +137,33 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
 
     __shared__ u32x4 lds[STAGES * STAGE];
 
-    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (lid >= a.tiles) return;
-    const int per_group = a.row_tiles * a.col_tiles;
-    const int e = lid / per_group;
-    const int rem = lid - e * per_group;
-    const int ct = rem / a.row_tiles, rt = rem - ct * a.row_tiles;
-    const int rows = a.rows_valid ? min(a.rows_valid[e], a.Mrows) : a.Mrows;
-    if (rt * BM >= rows) return;
-    const int kv = a.k_valid ? min(a.k_valid[e], a.K) : a.K;
-    const int slabs = (kv + BK - 1) / BK;
-
-    const E *X = a.x + (size_t)e * a.sx;
-    const E *W = a.w + (size_t)e * a.sw;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WGM, wn = wave / WGM;
+    // ---- which tile(s): one per workgroup (plain grid, ids remapped so that each XCD gets a contiguous range) or
+    // PERSIST: one workgroup per slot of the chip walks the live tiles (LiveTileWalk) and requests the first
+    // slabs of its next tile before the epilogue of the current one (PREFETCH), which then stages its output in
+    // the one pipeline buffer those loads do not touch.
+    constexpr bool PREFETCH = PERSIST && OROWS * OSTRIDE <= STAGE;
+    constexpr int STG = PREFETCH ? (STAGES - 1) * STAGE : 0;   // staging area, in 16-byte units
+    LiveTileWalk<BM> walk;
+    if constexpr (PERSIST) walk.init(a.rows_valid, a.N, a.Mrows, a.col_tiles);
+    struct Tile {
+        int e, rt, ct, rows, kv;
+    };
+    auto select = [&](Tile &t) {
+        if constexpr (PERSIST) {
+            if (!walk.tile(t.e, t.rt, t.ct)) return false;
+        } else {
+            const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
+            const int lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+            if (lid >= a.tiles) return false;
+            const int per_group = a.row_tiles * a.col_tiles;
+            t.e = lid / per_group;
+            const int rem = lid - t.e * per_group;
+            t.ct = rem / a.row_tiles, t.rt = rem - t.ct * a.row_tiles;
+        }
+        t.rows = a.rows_valid ? min(a.rows_valid[t.e], a.Mrows) : a.Mrows;
+        t.kv = a.k_valid ? min(a.k_valid[t.e], a.K) : a.K;
+        return t.rt * BM < t.rows;
+    };
 
     // ---- loader: this lane's source of each of the wave's load instructions (slab 0), the k-row it
     // holds (transposed operands; -1 otherwise) and its advance per slab
@@ -164,28 +175,57 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
     constexpr bool KRAGGED = XT && WT;
     const E *src[GPW];
     int krow[GPW];
+    int kv = 0;   // contraction length of the tile whose loads are being issued
     const size_t adv_x = XT ? (size_t)BK * a.ldx : (size_t)BK, adv_w = WT ? (size_t)BK * a.ldw : (size_t)BK;
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-        const int inst = wave + i * NW;
-        if (i < XG) {
-            // a transposed x holds the output rows along its fast index: all Mrows columns exist in memory
-            src[i] = XTile::source(X, inst * 64 + lane, rt * BM, XT ? a.Mrows : rows, a.ldx, krow[i]);
-        } else {
-            src[i] = WTile::source(W, (inst - XI) * 64 + lane, ct * BN, a.Nout, a.ldw, krow[i]);
-        }
-    }
     const E *zero = reinterpret_cast<const E *>(kZeroPiece);
     // load instruction i of slab `slab` into `stage`
-    auto load_one = [&](int i, int slab, int stage) {
+    auto load_one = [&](int wave, int i, int slab, int stage) {
         const E *p = src[i] + (size_t)slab * (i < XG ? adv_x : adv_w);
         if (KRAGGED && slab * BK + krow[i] >= kv) p = zero;   // beyond the contraction length
         __builtin_amdgcn_global_load_lds(SMILE_GPTR(p), SMILE_LPTR(&lds[stage * STAGE + (wave + i * NW) * 64]), 16, 0, 0);
     };
-    auto issue = [&](int slab, int stage) {
-#pragma unroll
-        for (int i = 0; i < GPW; ++i) load_one(i, slab, stage);
+    // Per-lane indices are derived afresh wherever they are needed (PERSIST: through an opaque copy of the
+    // thread id), so that nothing computed from them stays in registers from one tile to the next.
+    auto thread_id = [&]() {
+        int tid = threadIdx.x;
+        if constexpr (PERSIST) asm volatile("" : "+v"(tid));
+        return tid;
     };
+    // source addresses of a tile and the requests for its first STAGES-1 slabs
+    auto start_tile = [&](const Tile &t) {
+        const int tid = thread_id(), lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const E *X = a.x + (size_t)t.e * a.sx;
+        const E *W = a.w + (size_t)t.e * a.sw;
+        kv = t.kv;
+        const int slabs = (t.kv + BK - 1) / BK;
+#pragma unroll
+        for (int i = 0; i < GPW; ++i) {
+            const int inst = wave + i * NW;
+            if (i < XG) {
+                // a transposed x holds the output rows along its fast index: all Mrows columns exist in memory
+                src[i] = XTile::source(X, inst * 64 + lane, t.rt * BM, XT ? a.Mrows : t.rows, a.ldx, krow[i]);
+            } else {
+                src[i] = WTile::source(W, (inst - XI) * 64 + lane, t.ct * BN, a.Nout, a.ldw, krow[i]);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < slabs) {
+#pragma unroll
+                for (int i = 0; i < GPW; ++i) load_one(wave, i, s, s);
+            }
+    };
+
+    Tile cur;
+    if (!select(cur)) return;
+    start_tile(cur);
+    for (;;) {
+    const int e = cur.e, rt = cur.rt, ct = cur.ct, rows = cur.rows;
+    const int slabs = (cur.kv + BK - 1) / BK;
+    const int tid = thread_id(), lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
 
     // ---- fragment addressing
     // normal: lane reads row (lane & 31), pieces 2*kk + (lane >> 5)
@@ -224,10 +264,6 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < slabs) issue(s, s);
-
     const bool wave_live = rt * BM + wm * WM < rows;   // wave-uniform
     int stage = 0;
     // One K slab.  ISSUE: this iteration also issues the loads of slab kt+STAGES-1.  As in the forward kernel
@@ -236,50 +272,53 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
     auto slab_step = [&](auto issue_tag, int kt) {
         constexpr bool ISSUE = decltype(issue_tag)::value;
         if (ISSUE) {
-            wait_vmcnt<(STAGES - 2) * GPW>();
+            // a prefetched tile's first slabs were requested before the previous tile's stores: wait for all
+            if (PREFETCH && STAGES > 2 && kt == 0) wait_vmcnt<0>();
+            else wait_vmcnt<(STAGES - 2) * GPW>();
         } else {
             const int ahead = slabs - 1 - kt;   // 0 .. STAGES-2 slabs were issued after this one
-            if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
+            if (PREFETCH && kt == 0) wait_vmcnt<0>();
+            else if (STAGES >= 4 && ahead == 2) wait_vmcnt<2 * GPW>();
             else if (STAGES >= 3 && ahead == 1) wait_vmcnt<GPW>();
             else wait_vmcnt<0>();
         }
         __builtin_amdgcn_s_barrier();
         const int nstage = stage == 0 ? STAGES - 1 : stage - 1;
         const int nxt = kt + STAGES - 1;
-        const char *cur = reinterpret_cast<const char *>(lds + stage * STAGE);
+        const char *cur_stage = reinterpret_cast<const char *>(lds + stage * STAGE);
         bf16x8 xf[2][TM], wf[2][TN];
         auto fetch = [&](int buf, int kk) {
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
                 if constexpr (XT) {
-                    const char *p = cur + xoff[j] + kk * 16 * XTile::kPiecesPerK * 16;
+                    const char *p = cur_stage + xoff[j] + kk * 16 * XTile::kPiecesPerK * 16;
                     struct { s16x4 lo, hi; } t;
                     t.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
                     t.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (__attribute__((address_space(3))) s16x4 *)(p + 4 * XTile::kPiecesPerK * 16));
                     xf[buf][j] = __builtin_bit_cast(bf16x8, t);
                 } else {
-                    xf[buf][j] = *reinterpret_cast<const bf16x8 *>(cur + xoff[j] + (((2 * kk + fhi) ^ fsw) * 16));
+                    xf[buf][j] = *reinterpret_cast<const bf16x8 *>(cur_stage + xoff[j] + (((2 * kk + fhi) ^ fsw) * 16));
                 }
             }
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
                 if constexpr (WT) {
-                    const char *p = cur + woff[i] + kk * 16 * WTile::kPiecesPerK * 16;
+                    const char *p = cur_stage + woff[i] + kk * 16 * WTile::kPiecesPerK * 16;
                     struct { s16x4 lo, hi; } t;
                     t.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
                     t.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (__attribute__((address_space(3))) s16x4 *)(p + 4 * WTile::kPiecesPerK * 16));
                     wf[buf][i] = __builtin_bit_cast(bf16x8, t);
                 } else {
-                    wf[buf][i] = *reinterpret_cast<const bf16x8 *>(cur + woff[i] + (((2 * kk + fhi) ^ fsw) * 16));
+                    wf[buf][i] = *reinterpret_cast<const bf16x8 *>(cur_stage + woff[i] + (((2 * kk + fhi) ^ fsw) * 16));
                 }
             }
         };
         auto issue_part = [&](int l0, int l1) {
 #pragma unroll
             for (int i = 0; i < GPW; ++i)
-                if (i >= l0 && i < l1) load_one(i, nxt, nstage);
+                if (i >= l0 && i < l1) load_one(wave, i, nxt, nstage);
         };
         constexpr int KS = BK / 16;
         if (!wave_live) {
@@ -318,14 +357,22 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
     for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
     for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
 
+    Tile nxt_tile;
+    bool more = false;
+    if constexpr (PERSIST) {
+        walk.advance();
+        more = select(nxt_tile);
+    }
+
     // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4, row lane%32)
     // of its 32x32 tile: rounded to bf16, staged as a [OROWS][BN] tile, stored row-contiguously.
     E *Y = a.y + (size_t)e * a.sy;
-    u32x2 *stg = reinterpret_cast<u32x2 *>(lds);
+    u32x2 *stg = reinterpret_cast<u32x2 *>(lds + STG);
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads are done
         __builtin_amdgcn_s_barrier();
+        if (PREFETCH && j == 0 && more) start_tile(nxt_tile);
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -344,7 +391,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
             const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
             const int col = ct * BN + piece * 8;
             if (row < rows && col < a.Nout) {
-                u32x4 v = lds[orow * OSTRIDE + piece];
+                u32x4 v = lds[STG + orow * OSTRIDE + piece];
                 if constexpr (POST != 0) {
                     const u32x4 p = *reinterpret_cast<const u32x4 *>(a.aux + (size_t)e * a.sy + (size_t)row * a.Nout + col);
 #pragma unroll
@@ -356,6 +403,15 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
             }
         }
     }
+    if (!more) return;
+    if constexpr (!PREFETCH) {
+        // the next tile's first loads overwrite the staging area: every wave must be done reading it
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        start_tile(nxt_tile);
+    }
+    cur = nxt_tile;
+    }   // tile loop
 }
 
 template <typename E, int BM, int BN, int STAGES, int OCC, bool XT, bool WT, int POST>
@@ -364,9 +420,16 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
     a.row_tiles = (a.Mrows + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
-    const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
-                       dim3(256), 0, s, a);
+    a.N = N;
+    constexpr int slots = workgroup_slots(4, OCC, STAGES * (BM + BN) * BK * 2);
+    if (use_persistent_grid(N, a.tiles, slots)) {
+        hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST, true>), dim3(slots), dim3(256),
+                           0, s, a);
+    } else {
+        const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
+        hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
+                           dim3(256), 0, s, a);
+    }
     return hipGetLastError();
 }
 
@@ -395,7 +458,7 @@ hipError_t launch_typed(const TransposedGemm &g, hipStream_t s)
 {
     TGemmArgs<E> a{static_cast<const E *>(g.x), static_cast<const E *>(g.w), static_cast<E *>(g.y),
                    static_cast<const E *>(g.aux), g.rows_valid, g.k_valid, g.Mrows, g.Nout, g.K, g.ldx, g.ldw,
-                   g.sx, g.sw, g.sy, 0, 0, 0};
+                   g.sx, g.sw, g.sy, 0, 0, 0, g.N};
     if (g.x_transposed) return launch_shape<E, true, true, 0>(a, g.N, s);
     if (g.post == 1) return launch_shape<E, false, true, 1>(a, g.N, s);
     if (g.post == 2) return launch_shape<E, false, true, 2>(a, g.N, s);

@@ -131,6 +131,97 @@ __device__ __forceinline__ float wave_sum_column(const float *__restrict__ part,
     return s;
 }
 
+// Walk of a persistent workgroup over the LIVE tiles of a grouped GEMM whose groups (experts) have ragged,
+// device-resident row counts: row tile rt of group e is live when rt*BM < rows[e].  The grid is one workgroup per
+// slot the chip can hold; tiles of empty buffer rows are never scheduled (with a plain grid each of them is a
+// workgroup that has to wait for a free slot before it can exit).  Every wave finds the live row tiles for
+// itself, in registers, with no LDS and no extra launch: lane c holds the live row tiles of groups 64c .. 64c+63
+// (hence N <= 4096) and the group of a ticket is located with two ballots.  Tickets are ordered (group, column
+// tile, row tile) so that the row tiles sharing a weight tile and the column tiles sharing a token tile run
+// side by side, and each of the 8 XCDs (own L2) takes a contiguous range of tickets; workgroup ids are dealt
+// round-robin to the XCDs by the hardware.  All results are wave-uniform and equal in every wave of a workgroup.
+template <int BM>
+struct LiveTileWalk {
+    const int32_t *rows;   // [N] or null: `cap` rows in every group
+    int N, cap, col_tiles;
+    int lane;
+    int chunk_tiles, chunk_incl;           // lane c: live row tiles of groups 64c..64c+63, and their inclusive prefix
+    int cur_chunk, cur_cnt, cur_incl;      // the chunk the last ticket fell in: lane l = group 64*cur_chunk + l
+    int ticket, ticket_end, ticket_step;
+
+    __device__ __forceinline__ int live_row_tiles(int g) const
+    {
+        if (g >= N) return 0;
+        const int r = rows ? min(max(rows[g], 0), cap) : cap;
+        return (r + BM - 1) / BM;
+    }
+    __device__ __forceinline__ int scan(int v) const   // inclusive prefix sum over the 64 lanes
+    {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(v, off, 64);
+            if (lane >= off) v += o;
+        }
+        return v;
+    }
+    __device__ __forceinline__ void init(const int32_t *rows_, int N_, int cap_, int col_tiles_)
+    {
+        rows = rows_, N = N_, cap = cap_, col_tiles = col_tiles_;
+        lane = threadIdx.x & 63;
+        chunk_tiles = 0, cur_chunk = -1, cur_cnt = 0, cur_incl = 0;
+        const int nchunks = (N + 63) / 64;
+        for (int c = 0; c < nchunks; ++c) {
+            int v = live_row_tiles(c * 64 + lane);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == c) chunk_tiles = v;
+        }
+        chunk_incl = scan(chunk_tiles);
+        const int tickets = __builtin_amdgcn_readlane(chunk_incl, 63) * col_tiles;
+        const int per_xcd = (tickets + 7) / 8, xcd = blockIdx.x % 8;
+        ticket = xcd * per_xcd + blockIdx.x / 8;
+        ticket_end = min(tickets, (xcd + 1) * per_xcd);
+        ticket_step = gridDim.x / 8;
+    }
+    // the tile of the current ticket; false when this workgroup has no ticket left
+    __device__ __forceinline__ bool tile(int &e, int &rt, int &ct)
+    {
+        if (ticket >= ticket_end) return false;
+        const int I = ticket / col_tiles;   // index of the live row tile
+        const int c = __builtin_ctzll(__ballot(chunk_incl > I));
+        const int cbase = __builtin_amdgcn_readlane(chunk_incl - chunk_tiles, c);
+        if (c != cur_chunk) {
+            cur_cnt = live_row_tiles(c * 64 + lane);
+            cur_incl = scan(cur_cnt);
+            cur_chunk = c;
+        }
+        const int l = __builtin_ctzll(__ballot(cbase + cur_incl > I));
+        const int first = cbase + __builtin_amdgcn_readlane(cur_incl - cur_cnt, l);
+        const int cnt = __builtin_amdgcn_readlane(cur_cnt, l);
+        const int u = ticket - first * col_tiles;   // 0 .. cnt*col_tiles-1, row tile fastest
+        e = c * 64 + l;
+        ct = u / cnt;
+        rt = u - ct * cnt;
+        return true;
+    }
+    __device__ __forceinline__ void advance() { ticket += ticket_step; }
+};
+
+// Workgroup slots of the chip for a kernel of `waves` waves per workgroup that was compiled for `occ` waves per SIMD
+// and uses `lds_bytes` of LDS: 256 CUs x min(register budget, LDS budget).
+constexpr int kCus = 256, kLdsPerCu = 160 * 1024;
+constexpr int workgroup_slots(int waves, int occ, int lds_bytes)
+{
+    const int by_regs = occ * 4 / waves > 0 ? occ * 4 / waves : 1;
+    const int by_lds = kLdsPerCu / lds_bytes;
+    return kCus * (by_regs < by_lds ? by_regs : by_lds);
+}
+
+// Persistent launch or the plain grid?  Persistent when the plain grid would be several times the number of slots:
+// then workgroups of empty buffer rows would take turns with the live ones.  With at most a few tiles per slot the
+// two are equal within 1-2 %.  The environment variable SMILE_FFN_PERSIST=0/1 overrides the choice for tuning runs.
+bool use_persistent_grid(int N, long long tiles, int slots);
+
 }  // namespace smile
 
 struct smile_ctx {
