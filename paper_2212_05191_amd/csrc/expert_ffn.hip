@@ -340,13 +340,18 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
         }
         stage = stage + 1 == STAGES ? 0 : stage + 1;
     };
+    // the next tile is chosen before the main loop, so that the loads of its row counts are long back when
+    // the epilogue needs them (after it where registers are short: DUAL)
+    Tile nxt_tile;
+    bool more = false;
+    if constexpr (PERSIST && !DUAL) {
+        walk.advance();
+        more = select(nxt_tile);
+    }
     int kt = 0;
     for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
     for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
-
-    Tile nxt_tile;
-    bool more = false;
-    if constexpr (PERSIST) {
+    if constexpr (PERSIST && DUAL) {
         walk.advance();
         more = select(nxt_tile);
     }
@@ -385,12 +390,12 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
             }
             __builtin_amdgcn_s_waitcnt(0xC07F);
             __builtin_amdgcn_s_barrier();
-            for (int id = tid; id < OROWS * OPR; id += NT) {
+            // staged piece `id` (already read into v) -> global memory
+            auto store_piece = [&](int id, u32x4 v) {
                 const int orow = id / OPR, piece = id - orow * OPR;
                 const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
                 const int col = ct * BN + piece * 8;
-                if (row < rows && col < Nout) {
-                    u32x4 v = lds[STG + orow * OSTRIDE + piece];
+                if (id < OROWS * OPR && row < rows && col < Nout) {
                     if constexpr (POST != 0) {
                         const u32x4 p = *reinterpret_cast<const u32x4 *>(
                             static_cast<const E *>(a.aux) + ((size_t)e * a.C + row) * Nout + col);
@@ -406,6 +411,25 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
                             scale_x8<E>(v, a.gate[tok]);
                     }
                 }
+            };
+            if constexpr (DUAL) {
+                // the accumulators are needed again: registers are short, one piece at a time
+                for (int id = tid; id < OROWS * OPR; id += NT) {
+                    const int orow = id / OPR;
+                    store_piece(id, lds[STG + orow * OSTRIDE + id - orow * OPR]);
+                }
+            } else {
+                // all of the thread's staged pieces are read before the first store, so that the LDS latencies overlap
+                constexpr int NIT = (OROWS * OPR + NT - 1) / NT;
+                u32x4 outv[NIT];
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int id = min(tid + it * NT, OROWS * OPR - 1);
+                    const int orow = id / OPR;
+                    outv[it] = lds[STG + orow * OSTRIDE + id - orow * OPR];
+                }
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) store_piece(tid + it * NT, outv[it]);
             }
         }
     }

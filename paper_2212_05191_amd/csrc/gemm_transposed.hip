@@ -353,16 +353,17 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
         }
         stage = stage + 1 == STAGES ? 0 : stage + 1;
     };
-    int kt = 0;
-    for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
-    for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
-
+    // the next tile is chosen before the main loop, so that the loads of its row counts are long back when
+    // the epilogue needs them
     Tile nxt_tile;
     bool more = false;
     if constexpr (PERSIST) {
         walk.advance();
         more = select(nxt_tile);
     }
+    int kt = 0;
+    for (; kt + STAGES - 1 < slabs; ++kt) slab_step(std::true_type{}, kt);
+    for (; kt < slabs; ++kt) slab_step(std::false_type{}, kt);
 
     // ---- epilogue.  Accumulator element v of a lane is (column 8*(v/4) + 4*(lane/32) + v%4, row lane%32)
     // of its 32x32 tile: rounded to bf16, staged as a [OROWS][BN] tile, stored row-contiguously.
@@ -386,12 +387,23 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_s_barrier();
-        for (int id = tid; id < OROWS * OPR; id += NT) {
+        // all of the thread's staged pieces are read before the first store, so that the LDS latencies overlap
+        constexpr int NIT = (OROWS * OPR + NT - 1) / NT;
+        u32x4 outv[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int id = min(tid + it * NT, OROWS * OPR - 1);
+            const int orow = id / OPR, piece = id - orow * OPR;
+            outv[it] = lds[STG + orow * OSTRIDE + piece];
+        }
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int id = tid + it * NT;
             const int orow = id / OPR, piece = id - orow * OPR;
             const int row = rt * BM + (orow >> 5) * WM + j * 32 + (orow & 31);
             const int col = ct * BN + piece * 8;
-            if (row < rows && col < a.Nout) {
-                u32x4 v = lds[STG + orow * OSTRIDE + piece];
+            if (id < OROWS * OPR && row < rows && col < a.Nout) {
+                u32x4 v = outv[it];
                 if constexpr (POST != 0) {
                     const u32x4 p = *reinterpret_cast<const u32x4 *>(a.aux + (size_t)e * a.sy + (size_t)row * a.Nout + col);
 #pragma unroll
@@ -399,7 +411,10 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
                         v[k] = Half<E>::pack(Half<E>::lo(v[k]) * activate_grad<POST>(Half<E>::lo(p[k])),
                                              Half<E>::hi(v[k]) * activate_grad<POST>(Half<E>::hi(p[k])));
                 }
-                *reinterpret_cast<u32x4 *>(Y + (size_t)row * a.Nout + col) = v;
+                u32x4 *dst = reinterpret_cast<u32x4 *>(Y + (size_t)row * a.Nout + col);
+                // weight gradients are not read again soon: keep them out of the way of the operands in L2
+                if constexpr (KRAGGED) __builtin_nontemporal_store(v, dst);
+                else *dst = v;
             }
         }
     }
