@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsmile.so")
-SOURCES = ["smile_api.hip", "gate_logits.hip", "route.hip", "permute.hip", "expert_ffn.hip", "aux_loss.hip", "backward.hip", "gemm_transposed.hip"]
+SOURCES = ["smile_api.hip", "gate_logits.hip", "route.hip", "permute.hip", "expert_ffn.hip", "aux_loss.hip", "backward.hip", "gemm_transposed.hip",
+           "router_grad_mfma.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

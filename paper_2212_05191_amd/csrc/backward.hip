@@ -16,6 +16,8 @@
 //                          reduction over the blocks (bit-reproducible, no atomics)
 #include <type_traits>
 
+#include <cstdlib>
+
 #include "smile_internal.hpp"
 
 namespace smile {
@@ -491,6 +493,10 @@ hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, 
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s)
 {
+    // SMILE_ROUTER_GRAD_MFMA=0 keeps the vector-ALU kernels (tuning / comparison runs)
+    const char *env = std::getenv("SMILE_ROUTER_GRAD_MFMA");
+    if (dispatch_backward_mfma_applies(d) && !(env && env[0] == '0'))
+        return launch_dispatch_backward_mfma(d, dxe, group_idx, local_idx, slot, dlp, dlq, w_inter, w_intra, dx, s);
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
@@ -507,14 +513,23 @@ hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspa
 {
     const BackwardLayout L = backward_workspace_layout(d);
     float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_gw_partial);
-    const dim3 grid(L.gw_blocks, (d.d_model + kGwCols - 1) / kGwCols), block(kThreads);
-    SMILE_DTYPE_SWITCH(d.dtype, hipLaunchKernelGGL(gate_weights_partial_kernel<DT>, grid, block, 0, s, x, dlp, dlq,
-                                                   partial, d.T, d.d_model, d.n_groups, d.m_local));
-    hipError_t err = hipGetLastError();
+    int blocks = L.gw_blocks;
+    hipError_t err;
+    const char *env = std::getenv("SMILE_ROUTER_GRAD_MFMA");
+    if (gate_weights_mfma_applies(d) && !(env && env[0] == '0')) {
+        const int tokens = gate_weights_mfma_block_tokens(d, kGwTokens);
+        blocks = (d.T + tokens - 1) / tokens;   // <= L.gw_blocks: the partial sums fit the same scratch area
+        err = launch_gate_weights_mfma(d, x, dlp, dlq, partial, blocks, tokens, s);
+    } else {
+        const dim3 grid(L.gw_blocks, (d.d_model + kGwCols - 1) / kGwCols), block(kThreads);
+        SMILE_DTYPE_SWITCH(d.dtype, hipLaunchKernelGGL(gate_weights_partial_kernel<DT>, grid, block, 0, s, x, dlp, dlq,
+                                                       partial, d.T, d.d_model, d.n_groups, d.m_local));
+        err = hipGetLastError();
+    }
     if (err != hipSuccess) return err;
     const long long total = (long long)(d.n_groups + d.m_local) * d.d_model;
     hipLaunchKernelGGL(gate_weights_reduce_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
-                       partial, dw_inter, dw_intra, L.gw_blocks, d.d_model, d.n_groups, d.m_local);
+                       partial, dw_inter, dw_intra, blocks, d.d_model, d.n_groups, d.m_local);
     return hipGetLastError();
 }
 

@@ -353,6 +353,17 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
 hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s);
+// bf16 storage and at most 10 chunks of 16 logit columns: the same product on the matrix cores
+bool dispatch_backward_mfma_applies(const smile_layer_desc &d);
+hipError_t launch_dispatch_backward_mfma(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
+                                         const int32_t *local_idx, const int32_t *slot, const float *dlp,
+                                         const float *dlq, const void *w_inter, const void *w_intra, void *dx,
+                                         hipStream_t s);
+// bf16 storage and at most 160 logit columns: the per-block partial sums on the matrix cores
+bool gate_weights_mfma_applies(const smile_layer_desc &d);
+int gate_weights_mfma_block_tokens(const smile_layer_desc &d, int granule);
+hipError_t launch_gate_weights_mfma(const smile_layer_desc &d, const void *x, const float *dlp, const float *dlq,
+                                    float *partial, int blocks, int tokens_per_block, hipStream_t s);
 hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspace, const void *x, const float *dlp,
                                         const float *dlq, float *dw_inter, float *dw_intra, hipStream_t s);
 

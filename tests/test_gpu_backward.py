@@ -149,6 +149,13 @@ BACKWARD_CASES = [
     wl.small_config("bwd_bf16_long_ragged", 4099, 128, 256, 2, 4, 700, "bf16", "gelu", skew=True, seed=52),
     wl.small_config("bwd_f16_gelu", 3000, 192, 320, 3, 4, 200, "f16", "gelu", seed=53),
     wl.small_config("bwd_f16_relu_skew", 2500, 128, 448, 4, 8, 90, "f16", "relu", skew=True, seed=54),
+    # wide routers: the matrix-core kernels of the two router-weight products run with 5, 7 and 10 chunks of 16
+    # logit columns and 2, 4 and 5 tiles of 32 (d not a multiple of 256, T not a multiple of 64), and the
+    # widest case falls back to the vector-ALU kernels
+    wl.small_config("bwd_router_40x24", 1100, 192, 128, 40, 24, 9, "bf16", "gelu", seed=56),
+    wl.small_config("bwd_router_96x8", 1300, 320, 64, 96, 8, 6, "bf16", "relu", seed=57),
+    wl.small_config("bwd_router_flat_129", 1000, 576, 64, 1, 129, 20, "bf16", "gelu", seed=58),
+    wl.small_config("bwd_router_flat_200", 900, 64, 64, 1, 200, 12, "bf16", "gelu", seed=59),
 ]
 
 
