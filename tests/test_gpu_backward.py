@@ -193,6 +193,36 @@ def test_chained_backward_equals_steps_and_repeats(torch_cuda, cfg):
         b.close()
 
 
+PERSISTENT_CASES = [
+    # ragged row tiles, several column tiles
+    wl.small_config("persist_ragged", 2600, 320, 448, 2, 3, 500, "bf16", "gelu", seed=61),
+    # 130 experts (three 64-expert chunks of the tile walk), many of them empty or nearly so, buffers mostly empty
+    wl.small_config("persist_130_experts_skew", 3000, 64, 128, 10, 13, 300, "bf16", "relu", skew=True, seed=62),
+    wl.small_config("persist_f16", 1500, 128, 192, 3, 4, 260, "f16", "gelu", seed=63),
+    # fewer live tiles than workgroups in the grid
+    wl.small_config("persist_few_tiles", 90, 64, 64, 2, 2, 140, "bf16", "gelu", seed=64),
+]
+
+
+@pytest.mark.parametrize("cfg", PERSISTENT_CASES, ids=lambda c: c.name)
+def test_persistent_grid_forward_and_backward(torch_cuda, cfg, monkeypatch):
+    """The expert GEMMs launched as persistent workgroups that walk the live tiles (normally chosen only for grids
+    of many tiles), forced here on small ragged shapes: forward (both paths) and backward against the oracle."""
+    monkeypatch.setenv("SMILE_FFN_PERSIST", "1")
+    layer = _forward_backward(cfg, dloss=0.7)
+    try:
+        _say(f"   forward {parity.check_full(cfg, layer)}")
+        y_ref = layer.buf.y.clone()
+        layer.buf.y.fill_(-1)
+        layer.forward_fused()
+        torch_cuda.cuda.synchronize()
+        assert bool((layer.buf.y == y_ref).all()), "fused forward differs from the materialised one"
+        _, _, info = _check_steps(cfg, layer, dloss=0.7)
+        _say(f"   steps {({k: float(f'{v:.2e}') for k, v in info.items()})}")
+    finally:
+        layer.close()
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_every_gradient_gemm_tile_shape(torch_cuda, tile, monkeypatch):
     """Each tile shape of the transposed-operand GEMM on a shape with ragged tiles in every direction."""
