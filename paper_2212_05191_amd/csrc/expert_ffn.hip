@@ -189,7 +189,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_nt_kernel(Gem
     constexpr bool PREFETCH = PERSIST && OROWS * OSTRIDE <= STAGE;
     constexpr int STG = PREFETCH ? (STAGES - 1) * STAGE : 0;   // staging area, in 16-byte units
     LiveTileWalk<BM> walk;
-    if constexpr (PERSIST) walk.init(a.kept, a.N, a.C, a.col_tiles);
+    if constexpr (PERSIST) walk.init(a.kept, a.N, a.C, a.col_tiles, false);
     struct Tile {
         int e, rt, ct, rows;
     };

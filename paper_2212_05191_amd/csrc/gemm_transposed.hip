@@ -144,7 +144,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
     constexpr bool PREFETCH = PERSIST && OROWS * OSTRIDE <= STAGE;
     constexpr int STG = PREFETCH ? (STAGES - 1) * STAGE : 0;   // staging area, in 16-byte units
     LiveTileWalk<BM> walk;
-    if constexpr (PERSIST) walk.init(a.rows_valid, a.N, a.Mrows, a.col_tiles);
+    if constexpr (PERSIST) walk.init(a.rows_valid, a.N, a.Mrows, a.col_tiles, XT && WT);
     struct Tile {
         int e, rt, ct, rows, kv;
     };

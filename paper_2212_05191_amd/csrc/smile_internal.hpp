@@ -138,8 +138,12 @@ __device__ __forceinline__ float wave_sum_column(const float *__restrict__ part,
 // itself, in registers, with no LDS and no extra launch: lane c holds the live row tiles of groups 64c .. 64c+63
 // (hence N <= 4096) and the group of a ticket is located with two ballots.  Tickets are ordered (group, column
 // tile, row tile) so that the row tiles sharing a weight tile and the column tiles sharing a token tile run
-// side by side, and each of the 8 XCDs (own L2) takes a contiguous range of tickets; workgroup ids are dealt
-// round-robin to the XCDs by the hardware.  All results are wave-uniform and equal in every wave of a workgroup.
+// side by side.  The 8 XCDs (own L2 each; workgroup ids are dealt round-robin to them by the hardware) take
+// chunks of consecutive tickets in turn.  One chunk per XCD (a contiguous eighth of the tickets) keeps the tiles that
+// share operands in one L2 and is what the forward GEMMs want (interleaving their tickets costs 5-15 %).  Chunks of
+// 128 tickets (`interleave`) spread groups whose tiles cost more over all XCDs; the weight-gradient GEMMs, whose
+// contraction length is the group's row count, want that (13 % on a skewed 256-expert workload).
+// All results are wave-uniform and equal in every wave of a workgroup.
 template <int BM>
 struct LiveTileWalk {
     const int32_t *rows;   // [N] or null: `cap` rows in every group
@@ -147,7 +151,7 @@ struct LiveTileWalk {
     int lane;
     int chunk_tiles, chunk_incl;           // lane c: live row tiles of groups 64c..64c+63, and their inclusive prefix
     int cur_chunk, cur_cnt, cur_incl;      // the chunk the last ticket fell in: lane l = group 64*cur_chunk + l
-    int ticket, ticket_end, ticket_step;
+    int local, local_step, xcd, tickets, chunk;   // position in the XCD's own sequence of tickets; chunk size
 
     __device__ __forceinline__ int live_row_tiles(int g) const
     {
@@ -164,7 +168,7 @@ struct LiveTileWalk {
         }
         return v;
     }
-    __device__ __forceinline__ void init(const int32_t *rows_, int N_, int cap_, int col_tiles_)
+    __device__ __forceinline__ void init(const int32_t *rows_, int N_, int cap_, int col_tiles_, bool interleave)
     {
         rows = rows_, N = N_, cap = cap_, col_tiles = col_tiles_;
         lane = threadIdx.x & 63;
@@ -177,16 +181,18 @@ struct LiveTileWalk {
             if (lane == c) chunk_tiles = v;
         }
         chunk_incl = scan(chunk_tiles);
-        const int tickets = __builtin_amdgcn_readlane(chunk_incl, 63) * col_tiles;
-        const int per_xcd = (tickets + 7) / 8, xcd = blockIdx.x % 8;
-        ticket = xcd * per_xcd + blockIdx.x / 8;
-        ticket_end = min(tickets, (xcd + 1) * per_xcd);
-        ticket_step = gridDim.x / 8;
+        tickets = __builtin_amdgcn_readlane(chunk_incl, 63) * col_tiles;
+        chunk = interleave ? 128 : max(1, (tickets + 7) / 8);
+        xcd = blockIdx.x % 8;
+        local = blockIdx.x / 8;
+        local_step = gridDim.x / 8;
     }
     // the tile of the current ticket; false when this workgroup has no ticket left
     __device__ __forceinline__ bool tile(int &e, int &rt, int &ct)
     {
-        if (ticket >= ticket_end) return false;
+        // the XCD's local-th ticket: chunk (local / chunk) * 8 + xcd, offset local % chunk; increasing in local
+        const int ticket = ((local / chunk) * 8 + xcd) * chunk + local % chunk;
+        if (ticket >= tickets) return false;
         const int I = ticket / col_tiles;   // index of the live row tile
         const int c = __builtin_ctzll(__ballot(chunk_incl > I));
         const int cbase = __builtin_amdgcn_readlane(chunk_incl - chunk_tiles, c);
@@ -204,7 +210,7 @@ struct LiveTileWalk {
         rt = u - ct * cnt;
         return true;
     }
-    __device__ __forceinline__ void advance() { ticket += ticket_step; }
+    __device__ __forceinline__ void advance() { local += local_step; }
 };
 
 // Workgroup slots of the chip for a kernel of `waves` waves per workgroup that was compiled for `occ` waves per SIMD
