@@ -140,9 +140,10 @@ __device__ __forceinline__ float wave_sum_column(const float *__restrict__ part,
 // tile, row tile) so that the row tiles sharing a weight tile and the column tiles sharing a token tile run
 // side by side.  The 8 XCDs (own L2 each; workgroup ids are dealt round-robin to them by the hardware) take
 // chunks of consecutive tickets in turn.  One chunk per XCD (a contiguous eighth of the tickets) keeps the tiles that
-// share operands in one L2 and is what the forward GEMMs want (interleaving their tickets costs 5-15 %).  Chunks of
-// 128 tickets (`interleave`) spread groups whose tiles cost more over all XCDs; the weight-gradient GEMMs, whose
-// contraction length is the group's row count, want that (13 % on a skewed 256-expert workload).
+// share operands in one L2 and is what the forward GEMMs want (interleaving their tickets costs 5-15 %).  8 k
+// equal chunks of at most 128 tickets (`interleave`) spread groups whose tiles cost more over all XCDs; the
+// weight-gradient GEMMs, whose contraction length is the group's row count, want that (13 % on a skewed
+// 256-expert workload).
 // All results are wave-uniform and equal in every wave of a workgroup.
 template <int BM>
 struct LiveTileWalk {
@@ -182,7 +183,9 @@ struct LiveTileWalk {
         }
         chunk_incl = scan(chunk_tiles);
         tickets = __builtin_amdgcn_readlane(chunk_incl, 63) * col_tiles;
-        chunk = interleave ? 128 : max(1, (tickets + 7) / 8);
+        // 8 k chunks of equal size: k = 1 (contiguous eighths), or enough for chunks of at most 128 tickets
+        const int k = interleave ? max(1, (tickets + 1023) / 1024) : 1;
+        chunk = max(1, (tickets + 8 * k - 1) / (8 * k));
         xcd = blockIdx.x % 8;
         local = blockIdx.x / 8;
         local_step = gridDim.x / 8;
