@@ -175,11 +175,16 @@ struct LiveTileWalk {
         lane = threadIdx.x & 63;
         chunk_tiles = 0, cur_chunk = -1, cur_cnt = 0, cur_incl = 0;
         const int nchunks = (N + 63) / 64;
-        for (int c = 0; c < nchunks; ++c) {
-            int v = live_row_tiles(c * 64 + lane);
+        for (int c0 = 0; c0 < nchunks; c0 += 4) {   // four chunks at a time: their loads overlap
+            int v[4];
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-            if (lane == c) chunk_tiles = v;
+            for (int u = 0; u < 4; ++u) v[u] = live_row_tiles((c0 + u) * 64 + lane);   // 0 beyond N
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) v[u] += __shfl_xor(v[u], off, 64);
+                if (lane == c0 + u) chunk_tiles = v[u];
+            }
         }
         chunk_incl = scan(chunk_tiles);
         tickets = __builtin_amdgcn_readlane(chunk_incl, 63) * col_tiles;

@@ -199,6 +199,8 @@ PERSISTENT_CASES = [
     # 130 experts (three 64-expert chunks of the tile walk), many of them empty or nearly so, buffers mostly empty
     wl.small_config("persist_130_experts_skew", 3000, 64, 128, 10, 13, 300, "bf16", "relu", skew=True, seed=62),
     wl.small_config("persist_f16", 1500, 128, 192, 3, 4, 260, "f16", "gelu", seed=63),
+    # 520 experts: the walk's per-lane table spans nine chunks of 64 experts
+    wl.small_config("persist_520_experts", 4000, 64, 64, 20, 26, 24, "bf16", "gelu", skew=True, seed=65),
     # fewer live tiles than workgroups in the grid
     wl.small_config("persist_few_tiles", 90, 64, 64, 2, 2, 140, "bf16", "gelu", seed=64),
 ]
