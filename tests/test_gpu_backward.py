@@ -193,6 +193,29 @@ def test_chained_backward_equals_steps_and_repeats(torch_cuda, cfg):
         b.close()
 
 
+@pytest.mark.parametrize("cfg", [BACKWARD_CASES[3], BACKWARD_CASES[14], BACKWARD_CASES[16]], ids=lambda c: c.name)
+def test_matrix_core_router_gradients_match_the_fma_kernels(torch_cuda, cfg, monkeypatch):
+    """dx and the router-weight gradients from the matrix-core kernels (logit gradients as three bf16 planes) against
+    the vector-ALU kernels (fp32 FMAs): the fp32 gradients agree to fp32 rounding of the sums, dx to one bf16
+    rounding step of the largest element."""
+    a = _forward_backward(cfg, chained=True)
+    monkeypatch.setenv("SMILE_ROUTER_GRAD_MFMA", "0")
+    b = _forward_backward(cfg, chained=True)
+    try:
+        oa, ob = _fetch_backward(a), _fetch_backward(b)
+        for k in ("dw_inter", "dw_intra"):
+            err = parity.normwise(oa[k], ob[k].astype(np.float64))
+            _say(f"   {k}: {err:.2e}")
+            assert err <= 2e-6, (k, err)
+        scale = float(np.abs(ob["dx"]).max())
+        diff = float(np.abs(oa["dx"].astype(np.float64) - ob["dx"]).max())
+        _say(f"   dx: max diff {diff:.3e} (max |dx| {scale:.3e})")
+        assert diff <= scale * 2.0 ** -8, (diff, scale)
+    finally:
+        a.close()
+        b.close()
+
+
 PERSISTENT_CASES = [
     # ragged row tiles, several column tiles
     wl.small_config("persist_ragged", 2600, 320, 448, 2, 3, 500, "bf16", "gelu", seed=61),
