@@ -111,10 +111,10 @@ __device__ __forceinline__ float softmax_z(const float *__restrict__ row, const 
     return z;
 }
 
-__device__ __forceinline__ void softmax_backward_row(const float *__restrict__ row, const float *__restrict__ bias,
+// (row and out may be the same array: element i of out is written after the last read of element i of row)
+__device__ __forceinline__ void softmax_backward_row(const float *row, const float *__restrict__ bias,
                                                      int len, int top, float mx, float inv_z, float coef,
-                                                     const int32_t *__restrict__ count, float extra,
-                                                     float *__restrict__ out)
+                                                     const int32_t *__restrict__ count, float extra, float *out)
 {
     float dot = 0.f;
     for (int i = 0; i < len; ++i) {
@@ -147,6 +147,54 @@ __global__ __launch_bounds__(kThreads) void route_backward_kernel(
     const float dg = dgate[t];
     softmax_backward_row(rp, bias_inter, n, g, mx_p, iz_p, coef_inter, group_count, dg * iz_q, dlp + (size_t)t * n);
     softmax_backward_row(rq, bq, m, l, mx_q, iz_q, coef_intra, local_count, dg * iz_p, dlq + (size_t)t * m);
+}
+
+// The same arithmetic with coalesced memory traffic: a workgroup's logit rows are contiguous in memory, so they are
+// copied to LDS with consecutive lanes on consecutive addresses (a thread reading its own row straight from memory
+// touches one cache line per lane and instruction), the gradients replace them in place, and the tile is copied
+// back the same way.  Row strides in LDS are odd, so the per-token threads fall on distinct banks.
+__global__ __launch_bounds__(kThreads) void route_backward_tiled_kernel(
+    const float *__restrict__ logits_inter, const float *__restrict__ logits_intra,
+    const float *__restrict__ bias_inter, const float *__restrict__ bias_intra,
+    const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx, const float *__restrict__ dgate,
+    const int32_t *__restrict__ group_count, const int32_t *__restrict__ local_count,
+    int T, int n, int m, float coef_inter, float coef_intra, float *__restrict__ dlp, float *__restrict__ dlq,
+    int tokens_per_block)
+{
+    extern __shared__ float route_bwd_lds[];
+    const int sp = n | 1, sq = m | 1;
+    float *tp = route_bwd_lds, *tq = route_bwd_lds + (size_t)tokens_per_block * sp;
+    const int t0 = blockIdx.x * tokens_per_block, cnt = min(tokens_per_block, T - t0);
+    const float *gp = logits_inter + (size_t)t0 * n, *gq = logits_intra + (size_t)t0 * m;
+    // element i of the contiguous tile <-> (row i / len, column i % len), advanced without divisions
+    auto copy_tile = [&](auto to_lds, float *tile, int stride, const float *src, float *dst, int len) {
+        const int dr = kThreads / len, dc = kThreads % len;
+        int r = threadIdx.x / len, c = threadIdx.x % len;
+        for (int i = threadIdx.x; i < cnt * len; i += kThreads) {
+            if constexpr (decltype(to_lds)::value) tile[r * stride + c] = src[i];
+            else dst[i] = tile[r * stride + c];
+            r += dr, c += dc;
+            if (c >= len) c -= len, ++r;
+        }
+    };
+    copy_tile(std::true_type{}, tp, sp, gp, nullptr, n);
+    copy_tile(std::true_type{}, tq, sq, gq, nullptr, m);
+    __syncthreads();
+    if ((int)threadIdx.x < cnt) {
+        const int t = t0 + threadIdx.x;
+        const int g = group_idx[t], l = local_idx[t];
+        float *rp = tp + threadIdx.x * sp, *rq = tq + threadIdx.x * sq;
+        const float *bq = bias_intra ? bias_intra + (size_t)g * m : nullptr;
+        float mx_p, mx_q;
+        const float iz_p = 1.0f / softmax_z(rp, bias_inter, n, g, mx_p);   // = p[g]
+        const float iz_q = 1.0f / softmax_z(rq, bq, m, l, mx_q);           // = q[l]
+        const float dg = dgate[t];
+        softmax_backward_row(rp, bias_inter, n, g, mx_p, iz_p, coef_inter, group_count, dg * iz_q, rp);
+        softmax_backward_row(rq, bq, m, l, mx_q, iz_q, coef_intra, local_count, dg * iz_p, rq);
+    }
+    __syncthreads();
+    copy_tile(std::false_type{}, tp, sp, nullptr, dlp + (size_t)t0 * n, n);
+    copy_tile(std::false_type{}, tq, sq, nullptr, dlq + (size_t)t0 * m, m);
 }
 
 // ------------------------------------------------------------------------------------ transpose
@@ -420,6 +468,17 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
     // d(alpha * n * sum_i f_i P_i) / dp[t,i] = alpha * n * (count_i / T) / T
     const float inv_t2 = 1.0f / ((float)d.T * (float)d.T);
     const float ci = dloss * d.alpha * (float)d.n_groups * inv_t2, cq = dloss * d.beta * (float)d.m_local * inv_t2;
+    // tokens per workgroup of the tiled kernel: as many as keep its LDS tile within 64 KB; routers too wide even for
+    // 64 tokens take the kernel that reads its rows from memory
+    const size_t row_bytes = (size_t)((d.n_groups | 1) + (d.m_local | 1)) * sizeof(float);
+    int tokens = kThreads;
+    while (tokens >= 64 && tokens * row_bytes > 64 * 1024) tokens /= 2;
+    if (tokens >= 64 && d.n_groups + d.m_local >= 32) {   // narrower routers: measured faster from memory
+        hipLaunchKernelGGL(route_backward_tiled_kernel, dim3((d.T + tokens - 1) / tokens), dim3(kThreads),
+                           tokens * row_bytes, s, logits_inter, logits_intra, bias_inter, bias_intra, group_idx, local_idx,
+                           dgate, group_count, local_count, d.T, d.n_groups, d.m_local, ci, cq, dlp, dlq, tokens);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(route_backward_kernel, dim3((d.T + kThreads - 1) / kThreads), dim3(kThreads), 0, s, logits_inter,
                        logits_intra, bias_inter, bias_intra, group_idx, local_idx, dgate, group_count, local_count, d.T,
                        d.n_groups, d.m_local, ci, cq, dlp, dlq);
