@@ -36,17 +36,19 @@ __device__ __forceinline__ void split3(float v, __bf16 &hi, __bf16 &mid, __bf16 
 
 // ------------------------------------------------------------------------------------ dx
 
-constexpr int kDxCols = 256;     // columns of d per workgroup
+// columns of d per workgroup: 256, or 128 when the transposed weights of 256 would leave room for one workgroup per CU
+constexpr int dx_cols(int kc) { return kc <= 6 ? 256 : 128; }
 constexpr int kDxTokens = 128;   // tokens per workgroup: 32 per wave
 constexpr int kDxMaxChunks = 10; // 16-wide chunks of logit columns (inter, then intra) kept in registers
 
 // Row i of an MFMA A tile holds weight column perm(i) of the 32-column tile, so that a lane's 16 accumulator
-// elements are 16 CONSECUTIVE columns (16 * (lane >> 5) + v) of its token: two 16-byte loads / stores per tile.
+// elements are 16 CONSECUTIVE columns (16 * (lane >> 5) + v) of its token: two 16-byte pieces per tile.
 __device__ __forceinline__ int perm_col(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
 
-// Workgroup = 128 tokens x 256 columns.  The weight rows of the column range are transposed into LDS once
+// Workgroup = 128 tokens x 256 (or 128) columns.  The weight rows of the column range are transposed into LDS once
 // (wt[column][logit column], bf16); each wave splits the logit gradients of its 32 tokens into bf16 planes once
-// (registers) and then walks the eight 32-column tiles: KC*3 MFMAs, add the expert-buffer row, round, store.
+// (registers) and then walks the column range 64 columns at a time: 2*KC*3 MFMAs, add the expert-buffer row, round,
+// store; rows are read and written whole (128 bytes of a row per 8 lanes), through a per-wave LDS tile.
 template <int KC>
 __global__ __launch_bounds__(kThreads) void dispatch_backward_mfma_kernel(
     const __bf16 *__restrict__ dxe, const int32_t *__restrict__ group_idx, const int32_t *__restrict__ local_idx,
@@ -54,8 +56,10 @@ __global__ __launch_bounds__(kThreads) void dispatch_backward_mfma_kernel(
     const __bf16 *__restrict__ w_inter, const __bf16 *__restrict__ w_intra, __bf16 *__restrict__ dx, int T, int d,
     int n, int m, int C, int kp)
 {
+    constexpr int kDxCols = dx_cols(KC);
     constexpr int RS = KC * 16 + 8;   // row stride of wt in elements (+8: bank spread, keeps 16-byte alignment)
     __shared__ __attribute__((aligned(16))) __bf16 wt[kDxCols * RS];
+    __shared__ u32x4 io[kThreads / 64][32 * 9];   // per wave: 32 rows x 8 pieces (+1: bank spread)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c_base = blockIdx.y * kDxCols;
 
@@ -91,37 +95,71 @@ __global__ __launch_bounds__(kThreads) void dispatch_backward_mfma_kernel(
     }
     const int sl = t_ok ? slot[t] : -1;
     const __bf16 *src = sl >= 0 ? dxe + ((size_t)(group_idx[t] * m + local_idx[t]) * C + sl) * d : nullptr;
-    __bf16 *dst = dx + (size_t)t * d;
+
+    // ---- memory side: 64 columns (128 bytes of a row) at a time, whole rows per instruction.  Lane = (row lane / 8 +
+    // 8 it, 16-byte piece lane % 8) for it = 0..3; the rows' source pointers live in the lanes that own the tokens
+    // and are fetched from there once.  The tile goes through a per-wave LDS buffer to the lanes that hold the
+    // matching accumulators (token lane & 31, columns 32 u + 16 g + 8 h of the 64: piece 4 u + 2 g + h) and back.
+    const int mrow = lane >> 3, mpiece = lane & 7;
+    const __bf16 *msrc[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const unsigned long long p = reinterpret_cast<unsigned long long>(src);
+        const unsigned lo = __shfl((unsigned)p, mrow + 8 * it, 64), hi = __shfl((unsigned)(p >> 32), mrow + 8 * it, 64);
+        msrc[it] = reinterpret_cast<const __bf16 *>(((unsigned long long)hi << 32) | lo);
+    }
+    const int t_wave = blockIdx.x * kDxTokens + wave * 32;   // first token of the wave
+    u32x4 *tile = io[wave];
     __syncthreads();
 
     const int arow = perm_col(lane & 31);
-#pragma unroll 1
-    for (int ct = 0; ct < kDxCols / 32; ++ct) {
-        const int c0 = c_base + ct * 32;
-        if (c0 >= d) break;   // uniform
-        f32x16 acc;
+    u32x4 in[4];
+    auto fetch = [&](int c0) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-        for (int ch = 0; ch < KC; ++ch) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&wt[(ct * 32 + arow) * RS + ch * 16 + 8 * g]);
-#pragma unroll
-            for (int p = 0; p < 3; ++p) acc = Half<__bf16>::mfma_32x32x16(a, plane[ch][p], acc);
+        for (int it = 0; it < 4; ++it) {
+            in[it] = u32x4{0u, 0u, 0u, 0u};
+            if (msrc[it]) in[it] = *reinterpret_cast<const u32x4 *>(msrc[it] + c0 + mpiece * 8);
         }
-        // lane holds columns c0 + 16 g + 0..15 of token t
+    };
+    if (c_base < d) fetch(c_base);
+#pragma unroll 1
+    for (int cs = 0; cs < kDxCols / 64; ++cs) {
+        const int c0 = c_base + cs * 64;
+        if (c0 >= d) break;   // uniform (d is a multiple of 64)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int c = c0 + 16 * g + 8 * h;
-            if (t_ok && c < d) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (src) v = *reinterpret_cast<const u32x4 *>(src + c);
+        for (int it = 0; it < 4; ++it) tile[(mrow + 8 * it) * 9 + mpiece] = in[it];
+        if (c0 + 64 < d && cs + 1 < kDxCols / 64) fetch(c0 + 64);   // in flight during the MFMAs
+        f32x16 acc[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[u][v] = 0.f;
+#pragma unroll
+            for (int ch = 0; ch < KC; ++ch) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&wt[(cs * 64 + u * 32 + arow) * RS + ch * 16 + 8 * g]);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) acc[u] = Half<__bf16>::mfma_32x32x16(a, plane[ch][p], acc[u]);
+            }
+        }
+        // lane holds columns c0 + 32 u + 16 g + 0..15 of token (lane & 31): add the expert-buffer row, round once
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                u32x4 *cell = &tile[(lane & 31) * 9 + 4 * u + 2 * g + h];
+                const u32x4 v = *cell;
                 u32x4 o;
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
-                    o[k] = Half<__bf16>::pack(Half<__bf16>::lo(v[k]) + acc[8 * h + 2 * k],
-                                              Half<__bf16>::hi(v[k]) + acc[8 * h + 2 * k + 1]);
-                *reinterpret_cast<u32x4 *>(dst + c) = o;
+                    o[k] = Half<__bf16>::pack(Half<__bf16>::lo(v[k]) + acc[u][8 * h + 2 * k],
+                                              Half<__bf16>::hi(v[k]) + acc[u][8 * h + 2 * k + 1]);
+                *cell = o;
             }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = mrow + 8 * it;
+            const u32x4 o = tile[row * 9 + mpiece];
+            if (t_wave + row < T) *reinterpret_cast<u32x4 *>(dx + (size_t)(t_wave + row) * d + c0 + mpiece * 8) = o;
         }
     }
 }
@@ -131,7 +169,7 @@ hipError_t launch_dx(const smile_layer_desc &d, const void *dxe, const int32_t *
                      const int32_t *slot, const float *dlp, const float *dlq, const void *w_inter, const void *w_intra,
                      void *dx, int kp, hipStream_t s)
 {
-    const dim3 grid((d.T + kDxTokens - 1) / kDxTokens, (d.d_model + kDxCols - 1) / kDxCols), block(kThreads);
+    const dim3 grid((d.T + kDxTokens - 1) / kDxTokens, (d.d_model + dx_cols(KC) - 1) / dx_cols(KC)), block(kThreads);
     hipLaunchKernelGGL(dispatch_backward_mfma_kernel<KC>, grid, block, 0, s, static_cast<const __bf16 *>(dxe), group_idx,
                        local_idx, slot, dlp, dlq, static_cast<const __bf16 *>(w_inter),
                        static_cast<const __bf16 *>(w_intra), static_cast<__bf16 *>(dx), d.T, d.d_model, d.n_groups,
