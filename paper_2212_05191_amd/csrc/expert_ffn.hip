@@ -508,10 +508,11 @@ hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, hipSt
 //     one's prologue latency and activation epilogue;
 //   * down-projection (long K = d_ff, narrow output): a single workgroup per CU with a deeper ring
 //     wins -- four stages of 128x192 when the grid has at most one tile per CU, else three stages
-//     of 128x256 (fewer weight bytes through L2 per flop); with many experts of at most 256 buffer
-//     rows, 256x128 tiles (eight waves) so that every weight tile is streamed by exactly one
-//     workgroup even when the expert's buffer is full (12 % faster on the skewed 256-expert workload,
-//     equal on the uniform 128-expert one).
+//     of 128x256 (fewer weight bytes through L2 per flop).  256x128 tiles with eight waves (one tile per
+//     expert and column tile when buffers hold at most 256 rows) were the choice for many small buffers while
+//     every tile was a workgroup of its own; with the persistent walk over live tiles 128x256 is equal or
+//     better on every shape measured (256 experts at 21 % / 50 % / 95 % fill: 386 / 440 / 653 us against
+//     418 / 496 / 651), so they are only reachable through the override now.
 // Larger tiles (256x128 .. 256x256) move fewer bytes L2 -> LDS per flop but were never faster here.
 template <typename E>
 hipError_t launch_half_typed(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
@@ -538,8 +539,6 @@ int pick_tile(int N, int C, int Nout, int K)
         if (t >= 0 && t < kNumTiles) return t;
     }
     if (Nout >= K) return 0;
-    // many small expert buffers: one 256-row tile per (expert, column tile) streams each weight tile once
-    if (C <= 256 && (long long)N * ((Nout + 127) / 128) >= 1024) return 3;
     const long long tiles = (long long)N * ((C + 127) / 128) * ((Nout + 191) / 192);
     return tiles <= 256 ? 1 : 2;
 }
