@@ -451,13 +451,16 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
 // Tile shapes: id -> (BM, BN, stages, workgroups per CU).  Measured on the backward pass of the bf16
 // workloads: two co-resident workgroups with a two-stage ring beat one workgroup with a larger tile or a
 // deeper ring for all four products; 128 x 192 (fewer LDS bytes per MFMA) wins when it still gives every CU
-// its two workgroups, else 128 x 128.  The environment variable SMILE_TGEMM_TILE (0..3) overrides the choice
+// its two workgroups and does not pad the columns much, else 128 x 128.  The environment variable SMILE_TGEMM_TILE (0..3) overrides the choice
 // for tuning runs.
 template <typename E, bool XT, bool WT, int POST>
 hipError_t launch_shape(const TGemmArgs<E> &a, int N, hipStream_t s)
 {
     const long long wide = (long long)N * ((a.Mrows + 127) / 128) * ((a.Nout + 191) / 192);
     int tile = wide >= 512 ? 3 : 2;
+    // 192-wide column tiles that would be padded by more than a tenth over 128-wide ones (e.g. 1024 columns: 6 x 192
+    // against 8 x 128): the narrower tile wins (6 % on 64 experts of 320 x 1024 x 4096)
+    if ((a.Nout + 191) / 192 * 192 * 10 > (a.Nout + 127) / 128 * 128 * 11) tile = 2;
     if (const char *env = std::getenv("SMILE_TGEMM_TILE")) {
         const int t = std::atoi(env);
         if (t >= 0 && t <= 3) tile = t;
