@@ -34,6 +34,14 @@
  *     group capacity).  n = 1 (or m = 1) gives the flat one-level top-1
  *     router of Section 2 (Eq. 1-2, k = 1).
  *   - Floating-point inputs must be finite; NaN/Inf give unspecified results.
+ *   - Tuning switches (never needed in normal use; tests and sweeps set them): smile_create and
+ *     smile_create_with_workspace read the environment variables SMILE_FFN_TILE (0-6: tile shape of
+ *     the forward expert GEMMs), SMILE_TGEMM_TILE (0-3: tile shape of the gradient GEMMs),
+ *     SMILE_FFN_PERSIST (0/1: plain or persistent GEMM grid) and SMILE_ROUTER_GRAD_MFMA (0: vector-ALU
+ *     router-gradient kernels) ONCE and keep the values in the ctx; no other call looks at the
+ *     environment.  They change which kernel variant runs, never a result beyond rounding order.
+ *     The same two calls ask the runtime for the compute-unit count of the current device, which
+ *     sizes the persistent GEMM grids of that ctx.
  */
 #ifndef SMILE_H
 #define SMILE_H

@@ -1,29 +1,29 @@
-"""Build libsmile.so (HIP, gfx950) in-tree with hipcc."""
+"""Build libsmile.so (HIP, gfx950) in-tree with hipcc: one object per source, compiled side by side, then linked."""
 from __future__ import annotations
 
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsmile.so")
-SOURCES = ["smile_api.hip", "gate_logits.hip", "route.hip", "permute.hip", "expert_ffn.hip", "aux_loss.hip", "backward.hip", "gemm_transposed.hip",
-           "router_grad_mfma.hip"]
+PEAKS = os.path.join(HERE, "peaks_probe")
+SOURCES = ["smile_api.hip", "gate_logits.hip", "route.hip", "permute.hip", "expert_ffn.hip", "aux_loss.hip",
+           "backward.hip", "gemm_transposed.hip", "router_grad_mfma.hip"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # hipcc -O3 may form packed-fp32 instructions from scalar float code; keep them off
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -32,6 +32,21 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False, jobs: int | None = None) -> str:
+    """Compile every source (always: no staleness check) and link the library and the peak-rate probe."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    # the stand-alone microbenchmark of the chip's measured peak rates (no library code in it)
+    cmds.append([hipcc, *FLAGS, os.path.join(CSRC, "peaks_probe.hip"), "-o", PEAKS])
+    jobs = jobs or min(len(cmds), max(1, min(16, os.cpu_count() or 1)))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], verbose)
     return LIB
 
 

@@ -16,7 +16,6 @@
 //                          reduction over the blocks (bit-reproducible, no atomics)
 #include <type_traits>
 
-#include <cstdlib>
 
 #include "smile_internal.hpp"
 
@@ -485,7 +484,7 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
     return hipGetLastError();
 }
 
-hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace, const void *xe,
+hipError_t launch_expert_ffn_backward(const LayerDesc &d, void *workspace, const void *xe,
                                       const int32_t *kept_count, const void *w1, const void *w2, const void *dye,
                                       const void *h_saved, const void *pre_saved, void *dxe, void *dw1, void *dw2,
                                       hipStream_t s)
@@ -503,7 +502,7 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
     const void *h = h_saved, *pre = pre_saved;
     if (!h) {
         void *h_ws = b + L.off_h, *pre_ws = b + L.off_pre;
-        SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{xe, w1, h_ws, pre_ws, kept_count, N, C, F, dm, act}, s));
+        SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{xe, w1, h_ws, pre_ws, kept_count, N, C, F, dm, act, nullptr, nullptr, nullptr, 0, d.tune}, s));
         h = h_ws;
         pre = pre_ws;
     }
@@ -512,16 +511,16 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
         const long long cd = (long long)C * dm, cf = (long long)C * F, df = (long long)dm * F;
         // dpre[r,f] = (sum_c dye[r,c] W2[c,f]) * act'(pre[r,f])
         SMILE_TRY(launch_grouped_gemm_t(
-            d.dtype, TransposedGemm{dye, w2, dpre, pre, kept_count, nullptr, N, C, F, dm, dm, F, cd, df, cf, false, true, act}, s));
+            d.dtype, TransposedGemm{dye, w2, dpre, pre, kept_count, nullptr, N, C, F, dm, dm, F, cd, df, cf, false, true, act, d.tune}, s));
         // dW2[c,f] = sum_r dye[r,c] h[r,f]
         SMILE_TRY(launch_grouped_gemm_t(
-            d.dtype, TransposedGemm{dye, h, dw2, nullptr, nullptr, kept_count, N, dm, F, C, dm, F, cd, cf, df, true, true, 0}, s));
+            d.dtype, TransposedGemm{dye, h, dw2, nullptr, nullptr, kept_count, N, dm, F, C, dm, F, cd, cf, df, true, true, 0, d.tune}, s));
         // dxe[r,k] = sum_f dpre[r,f] W1[f,k]
         SMILE_TRY(launch_grouped_gemm_t(
-            d.dtype, TransposedGemm{dpre, w1, dxe, nullptr, kept_count, nullptr, N, C, dm, F, F, dm, cf, df, cd, false, true, 0}, s));
+            d.dtype, TransposedGemm{dpre, w1, dxe, nullptr, kept_count, nullptr, N, C, dm, F, F, dm, cf, df, cd, false, true, 0, d.tune}, s));
         // dW1[f,k] = sum_r dpre[r,f] xe[r,k]
         SMILE_TRY(launch_grouped_gemm_t(
-            d.dtype, TransposedGemm{dpre, xe, dw1, nullptr, nullptr, kept_count, N, F, dm, C, F, dm, cf, cd, df, true, true, 0}, s));
+            d.dtype, TransposedGemm{dpre, xe, dw1, nullptr, nullptr, kept_count, N, F, dm, C, F, dm, cf, cd, df, true, true, 0, d.tune}, s));
         return hipSuccess;
     }
     // fp32: the same four products on the x . w^T kernel, with explicitly transposed operands
@@ -531,30 +530,30 @@ hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace
         GroupedGemm g{dye, w_t, dpre, nullptr, kept_count, N, C, F, dm, 0};
         g.aux = pre;
         g.post = act;
+        g.tune = d.tune;
         SMILE_TRY(launch_grouped_gemm_nt(d.dtype, g, s));
     }
     // dW2[c][f] = sum_r dye[r][c] h[r][f]
     SMILE_TRY(transpose_pad(d.dtype, dye, dye_t, kept_count, N, C, dm, Kp, s));                 // [N][d][Kp]
     SMILE_TRY(transpose_pad(d.dtype, h, h_t, kept_count, N, C, F, Kp, s));                      // [N][F][Kp]
-    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dye_t, h_t, dw2, nullptr, nullptr, N, dm, F, Kp, 0}, s));
+    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dye_t, h_t, dw2, nullptr, nullptr, N, dm, F, Kp, 0, nullptr, nullptr, nullptr, 0, d.tune}, s));
     // dxe = dpre . W1   (W1 is [F][d])
     SMILE_TRY(transpose_pad(d.dtype, w1, w_t, nullptr, N, F, dm, F, s));                        // W1^T [N][d][F]
-    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dpre, w_t, dxe, nullptr, kept_count, N, C, dm, F, 0}, s));
+    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dpre, w_t, dxe, nullptr, kept_count, N, C, dm, F, 0, nullptr, nullptr, nullptr, 0, d.tune}, s));
     // dW1[f][k] = sum_r dpre[r][f] xe[r][k]
     SMILE_TRY(transpose_pad(d.dtype, dpre, dpre_t, kept_count, N, C, F, Kp, s));                // [N][F][Kp]
     SMILE_TRY(transpose_pad(d.dtype, xe, xe_t, kept_count, N, C, dm, Kp, s));                   // [N][d][Kp]
-    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dpre_t, xe_t, dw1, nullptr, nullptr, N, F, dm, Kp, 0}, s));
+    SMILE_TRY(launch_grouped_gemm_nt(d.dtype, GroupedGemm{dpre_t, xe_t, dw1, nullptr, nullptr, N, F, dm, Kp, 0, nullptr, nullptr, nullptr, 0, d.tune}, s));
 #undef SMILE_TRY
     return hipSuccess;
 }
 
-hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
+hipError_t launch_dispatch_backward(const LayerDesc &d, const void *dxe, const int32_t *group_idx,
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s)
 {
-    // SMILE_ROUTER_GRAD_MFMA=0 keeps the vector-ALU kernels (tuning / comparison runs)
-    const char *env = std::getenv("SMILE_ROUTER_GRAD_MFMA");
-    if (dispatch_backward_mfma_applies(d) && !(env && env[0] == '0'))
+    // Tuning::router_grad_mfma = 0 keeps the vector-ALU kernels (tuning / comparison runs)
+    if (dispatch_backward_mfma_applies(d) && d.tune.router_grad_mfma != 0)
         return launch_dispatch_backward_mfma(d, dxe, group_idx, local_idx, slot, dlp, dlq, w_inter, w_intra, dx, s);
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
@@ -567,15 +566,14 @@ hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, 
     return hipGetLastError();
 }
 
-hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspace, const void *x, const float *dlp,
+hipError_t launch_gate_weights_backward(const LayerDesc &d, void *workspace, const void *x, const float *dlp,
                                         const float *dlq, float *dw_inter, float *dw_intra, hipStream_t s)
 {
     const BackwardLayout L = backward_workspace_layout(d);
     float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_gw_partial);
     int blocks = L.gw_blocks;
     hipError_t err;
-    const char *env = std::getenv("SMILE_ROUTER_GRAD_MFMA");
-    if (gate_weights_mfma_applies(d) && !(env && env[0] == '0')) {
+    if (gate_weights_mfma_applies(d) && d.tune.router_grad_mfma != 0) {
         const int tokens = gate_weights_mfma_block_tokens(d, kGwTokens);
         blocks = (d.T + tokens - 1) / tokens;   // <= L.gw_blocks: the partial sums fit the same scratch area
         err = launch_gate_weights_mfma(d, x, dlp, dlq, partial, blocks, tokens, s);

@@ -38,7 +38,6 @@
 // LDS) before it can exit, in turn with the live ones.
 //
 // fp32 kernel (small / reference-precision configurations): classic LDS-tiled FMA GEMM.
-#include <cstdlib>
 #include <type_traits>
 
 #include <hip/hip_ext.h>
@@ -453,15 +452,15 @@ void launch_timed(Kernel k, dim3 grid, dim3 block, hipStream_t s, hipEvent_t t0,
 }
 
 template <typename E, int BM, int BN, int WGM, int WGN, int BK, int STAGES, int OCC = 1, int SWZ = 1>
-hipError_t launch_half_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
+hipError_t launch_half_tile(GemmArgs a, int N, int act, const Tuning &tune, hipStream_t s, hipEvent_t t0, hipEvent_t t1)
 {
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     a.N = N;
-    constexpr int slots = workgroup_slots(WGM * WGN, OCC, STAGES * (BM + BN) * BK * 2);
+    const int slots = workgroup_slots(tune, workgroups_per_cu(WGM * WGN, OCC, STAGES * (BM + BN) * BK * 2));
     const dim3 block(WGM * WGN * 64);
-    if (use_persistent_grid(N, a.tiles, slots)) {
+    if (use_persistent_grid(tune, N, a.tiles, slots)) {
         const dim3 grid(slots);
         if (act == 0) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 0, false, 0, true>, grid, block, s, t0, t1, a);
         else if (act == 1) launch_timed(grouped_gemm_nt_kernel<E, BM, BN, WGM, WGN, BK, STAGES, OCC, SWZ, 1, false, 0, true>, grid, block, s, t0, t1, a);
@@ -478,15 +477,15 @@ hipError_t launch_half_tile(GemmArgs a, int N, int act, hipStream_t s, hipEvent_
 // The two epilogue variants of the backward pass, on the up-projection tile shape only:
 //   a.y2 given: act(product) and the bare product in one launch;   post != 0: output times act'(a.aux).
 template <typename E>
-hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, hipStream_t s)
+hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, const Tuning &tune, hipStream_t s)
 {
     constexpr int BM = 128, BN = 192;
     a.row_tiles = (a.C + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     a.N = N;
-    constexpr int slots = workgroup_slots(4, 2, 2 * (BM + BN) * 64 * 2);
-    const bool persist = use_persistent_grid(N, a.tiles, slots);
+    const int slots = workgroup_slots(tune, workgroups_per_cu(4, 2, 2 * (BM + BN) * 64 * 2));
+    const bool persist = use_persistent_grid(tune, N, a.tiles, slots);
     const dim3 plain((a.tiles + kXcds - 1) / kXcds * kXcds), grid(persist ? dim3(slots) : plain), block(256);
     if (a.y2) {
         if (act == 1 && persist) hipLaunchKernelGGL((grouped_gemm_nt_kernel<E, BM, BN, 2, 2, 64, 2, 2, 1, 1, true, 0, true>), grid, block, 0, s, a);
@@ -515,29 +514,26 @@ hipError_t launch_half_special_typed(GemmArgs a, int N, int act, int post, hipSt
 //     418 / 496 / 651), so they are only reachable through the override now.
 // Larger tiles (256x128 .. 256x256) move fewer bytes L2 -> LDS per flop but were never faster here.
 template <typename E>
-hipError_t launch_half_typed(const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
-                       hipEvent_t t1 = nullptr)
+hipError_t launch_half_typed(const GemmArgs &a, int N, int act, int tile, const Tuning &tune, hipStream_t s,
+                             hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr)
 {
     switch (tile) {
-    case 0: return launch_half_tile<E, 128, 192, 2, 2, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 1: return launch_half_tile<E, 128, 192, 2, 2, 64, 4, 1>(a, N, act, s, t0, t1);
-    case 2: return launch_half_tile<E, 128, 256, 2, 2, 64, 3, 1>(a, N, act, s, t0, t1);
-    case 3: return launch_half_tile<E, 256, 128, 4, 2, 64, 3, 2>(a, N, act, s, t0, t1);
-    case 4: return launch_half_tile<E, 128, 128, 2, 2, 32, 4, 2>(a, N, act, s, t0, t1);
-    case 5: return launch_half_tile<E, 64, 256, 1, 4, 64, 2, 2>(a, N, act, s, t0, t1);
-    case 6: return launch_half_tile<E, 256, 256, 2, 4, 32, 4, 2>(a, N, act, s, t0, t1);
+    case 0: return launch_half_tile<E, 128, 192, 2, 2, 64, 2, 2>(a, N, act, tune, s, t0, t1);
+    case 1: return launch_half_tile<E, 128, 192, 2, 2, 64, 4, 1>(a, N, act, tune, s, t0, t1);
+    case 2: return launch_half_tile<E, 128, 256, 2, 2, 64, 3, 1>(a, N, act, tune, s, t0, t1);
+    case 3: return launch_half_tile<E, 256, 128, 4, 2, 64, 3, 2>(a, N, act, tune, s, t0, t1);
+    case 4: return launch_half_tile<E, 128, 128, 2, 2, 32, 4, 2>(a, N, act, tune, s, t0, t1);
+    case 5: return launch_half_tile<E, 64, 256, 1, 4, 64, 2, 2>(a, N, act, tune, s, t0, t1);
+    case 6: return launch_half_tile<E, 256, 256, 2, 4, 32, 4, 2>(a, N, act, tune, s, t0, t1);
     default: return hipErrorInvalidValue;
     }
 }
 constexpr int kNumTiles = 7;
 
-// Tile choice; the environment variable SMILE_FFN_TILE (0..6) overrides it for tuning runs.
-int pick_tile(int N, int C, int Nout, int K)
+// Tile choice; Tuning::ffn_tile (0..6) overrides it for tuning runs.
+int pick_tile(const Tuning &tune, int N, int C, int Nout, int K)
 {
-    if (const char *env = std::getenv("SMILE_FFN_TILE")) {
-        const int t = std::atoi(env);
-        if (t >= 0 && t < kNumTiles) return t;
-    }
+    if (tune.ffn_tile >= 0 && tune.ffn_tile < kNumTiles) return tune.ffn_tile;
     if (Nout >= K) return 0;
     const long long tiles = (long long)N * ((C + 127) / 128) * ((Nout + 191) / 192);
     return tiles <= 256 ? 1 : 2;
@@ -641,25 +637,25 @@ hipError_t launch_f32(const float *x, const float *w, const float *bias, float *
 
 
 // dtype dispatch of the two MFMA launchers
-hipError_t launch_half(int dtype, const GemmArgs &a, int N, int act, int tile, hipStream_t s, hipEvent_t t0 = nullptr,
-                       hipEvent_t t1 = nullptr)
+hipError_t launch_half(int dtype, const GemmArgs &a, int N, int act, int tile, const Tuning &tune, hipStream_t s,
+                       hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr)
 {
-    if (dtype == SMILE_DTYPE_BF16) return launch_half_typed<__bf16>(a, N, act, tile, s, t0, t1);
-    return launch_half_typed<_Float16>(a, N, act, tile, s, t0, t1);
+    if (dtype == SMILE_DTYPE_BF16) return launch_half_typed<__bf16>(a, N, act, tile, tune, s, t0, t1);
+    return launch_half_typed<_Float16>(a, N, act, tile, tune, s, t0, t1);
 }
 
-hipError_t launch_half_special(int dtype, const GemmArgs &a, int N, int act, int post, hipStream_t s)
+hipError_t launch_half_special(int dtype, const GemmArgs &a, int N, int act, int post, const Tuning &tune, hipStream_t s)
 {
-    if (dtype == SMILE_DTYPE_BF16) return launch_half_special_typed<__bf16>(a, N, act, post, s);
-    return launch_half_special_typed<_Float16>(a, N, act, post, s);
+    if (dtype == SMILE_DTYPE_BF16) return launch_half_special_typed<__bf16>(a, N, act, post, tune, s);
+    return launch_half_special_typed<_Float16>(a, N, act, post, tune, s);
 }
 
 }  // namespace
 
-bool use_persistent_grid(int N, long long tiles, int slots)
+bool use_persistent_grid(const Tuning &tune, int N, long long tiles, int slots)
 {
     if (N > 4096) return false;   // the tile walk keeps one lane per 64 groups
-    if (const char *env = std::getenv("SMILE_FFN_PERSIST")) return std::atoi(env) != 0;
+    if (tune.persist >= 0) return tune.persist != 0;
     return tiles >= 4LL * slots;
 }
 
@@ -670,8 +666,8 @@ hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s
     if (is_half(dtype)) {
         if (g.K % 64 || g.Nout % 8) return hipErrorInvalidValue;
         GemmArgs a{g.x, g.w, g.bias, g.y, g.kept, g.C, g.Nout, g.K, 0, 0, 0, g.x_rows, nullptr, nullptr, nullptr, g.y2, g.aux};
-        if (g.y2 || g.post) return launch_half_special(dtype, a, g.N, act, g.post, s);
-        return launch_half(dtype, a, g.N, act, pick_tile(g.N, g.C, g.Nout, g.K), s);
+        if (g.y2 || g.post) return launch_half_special(dtype, a, g.N, act, g.post, g.tune, s);
+        return launch_half(dtype, a, g.N, act, pick_tile(g.tune, g.N, g.C, g.Nout, g.K), g.tune, s);
     }
     if (g.K % 4) return hipErrorInvalidValue;
     return launch_f32(static_cast<const float *>(g.x), static_cast<const float *>(g.w),
@@ -680,7 +676,7 @@ hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s
                       static_cast<const float *>(g.aux), g.post);
 }
 
-hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
+hipError_t launch_expert_ffn_up(const LayerDesc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
                                 hipEvent_t t0, hipEvent_t t1, const void *x_tokens, void *h_save, void *pre_save)
 {
@@ -692,13 +688,14 @@ hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, 
     if (h_save) {   // training: the hidden activation and its pre-activation go to the caller's buffers
         if (t0 && t1) (void)hipEventRecord(t0, s);
         const hipError_t err = launch_grouped_gemm_nt(
-            d.dtype, GroupedGemm{src, w1, h_save, pre_save, kept_count, N, d.capacity, d.d_ff, d.d_model, act, b1, x_rows}, s);
+            d.dtype, GroupedGemm{src, w1, h_save, pre_save, kept_count, N, d.capacity, d.d_ff, d.d_model, act, b1, x_rows,
+                                 nullptr, 0, d.tune}, s);
         if (t0 && t1) (void)hipEventRecord(t1, s);
         return err;
     }
     if (is_half(d.dtype)) {
         GemmArgs g{src, w1, b1, ws.hidden, kept_count, d.capacity, d.d_ff, d.d_model, 0, 0, 0, x_rows, nullptr, nullptr, nullptr};
-        return launch_half(d.dtype, g, N, act, pick_tile(N, d.capacity, d.d_ff, d.d_model), s, t0, t1);
+        return launch_half(d.dtype, g, N, act, pick_tile(d.tune, N, d.capacity, d.d_ff, d.d_model), d.tune, s, t0, t1);
     }
     if (t0 && t1) (void)hipEventRecord(t0, s);
     const hipError_t err = launch_f32(static_cast<const float *>(src), static_cast<const float *>(w1),
@@ -708,7 +705,7 @@ hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, 
     return err;
 }
 
-hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
+hipError_t launch_expert_ffn_down(const LayerDesc &d, const Workspace &ws, const int32_t *kept_count,
                                   const void *w2, const void *b2, void *ye, hipStream_t s, void *y_tokens,
                                   const float *gate, const void *h_saved)
 {
@@ -718,7 +715,7 @@ hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws
     const int32_t *y_rows = y_tokens ? ws.slot_token : nullptr;
     if (is_half(d.dtype)) {
         GemmArgs g{hidden, w2, b2, ye, kept_count, d.capacity, d.d_model, d.d_ff, 0, 0, 0, nullptr, y_rows, y_tokens, gate};
-        return launch_half(d.dtype, g, N, 0, pick_tile(N, d.capacity, d.d_model, d.d_ff), s);
+        return launch_half(d.dtype, g, N, 0, pick_tile(d.tune, N, d.capacity, d.d_model, d.d_ff), d.tune, s);
     }
     return launch_f32(static_cast<const float *>(hidden), static_cast<const float *>(w2),
                       static_cast<const float *>(b2), static_cast<float *>(ye), kept_count, N, d.capacity,

@@ -28,7 +28,6 @@
 //     (no zero-padded copies, no work on empty buffer rows).
 //   * epilogue as in the forward kernel: fp32 -> bf16, staged through LDS, row-contiguous 16-byte
 //     stores; POST multiplies by act'(aux) there (the gradient at the pre-activation).
-#include <cstdlib>
 #include <type_traits>
 
 #include "smile_internal.hpp"
@@ -430,14 +429,14 @@ __global__ __launch_bounds__(WGM *WGN * 64, OCC) void grouped_gemm_t_kernel(TGem
 }
 
 template <typename E, int BM, int BN, int STAGES, int OCC, bool XT, bool WT, int POST>
-hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
+hipError_t launch_tile(TGemmArgs<E> a, int N, const Tuning &tune, hipStream_t s)
 {
     a.row_tiles = (a.Mrows + BM - 1) / BM;
     a.col_tiles = (a.Nout + BN - 1) / BN;
     a.tiles = N * a.row_tiles * a.col_tiles;
     a.N = N;
-    constexpr int slots = workgroup_slots(4, OCC, STAGES * (BM + BN) * BK * 2);
-    if (use_persistent_grid(N, a.tiles, slots)) {
+    const int slots = workgroup_slots(tune, workgroups_per_cu(4, OCC, STAGES * (BM + BN) * BK * 2));
+    if (use_persistent_grid(tune, N, a.tiles, slots)) {
         hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST, true>), dim3(slots), dim3(256),
                            0, s, a);
     } else {
@@ -451,24 +450,20 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, hipStream_t s)
 // Tile shapes: id -> (BM, BN, stages, workgroups per CU).  Measured on the backward pass of the bf16
 // workloads: two co-resident workgroups with a two-stage ring beat one workgroup with a larger tile or a
 // deeper ring for all four products; 128 x 192 (fewer LDS bytes per MFMA) wins when it still gives every CU
-// its two workgroups and does not pad the columns much, else 128 x 128.  The environment variable SMILE_TGEMM_TILE (0..3) overrides the choice
-// for tuning runs.
+// its two workgroups and does not pad the columns much, else 128 x 128.  Tuning::tgemm_tile (0..3) overrides the choice for tuning runs.
 template <typename E, bool XT, bool WT, int POST>
-hipError_t launch_shape(const TGemmArgs<E> &a, int N, hipStream_t s)
+hipError_t launch_shape(const TGemmArgs<E> &a, int N, const Tuning &tune, hipStream_t s)
 {
     const long long wide = (long long)N * ((a.Mrows + 127) / 128) * ((a.Nout + 191) / 192);
     int tile = wide >= 512 ? 3 : 2;
     // 192-wide column tiles that would be padded by more than a tenth over 128-wide ones (e.g. 1024 columns: 6 x 192
     // against 8 x 128): the narrower tile wins (6 % on 64 experts of 320 x 1024 x 4096)
     if ((a.Nout + 191) / 192 * 192 * 10 > (a.Nout + 127) / 128 * 128 * 11) tile = 2;
-    if (const char *env = std::getenv("SMILE_TGEMM_TILE")) {
-        const int t = std::atoi(env);
-        if (t >= 0 && t <= 3) tile = t;
-    }
-    if (tile == 0) return launch_tile<E, 128, 256, 3, 1, XT, WT, POST>(a, N, s);
-    if (tile == 1) return launch_tile<E, 128, 128, 4, 1, XT, WT, POST>(a, N, s);
-    if (tile == 2) return launch_tile<E, 128, 128, 2, 2, XT, WT, POST>(a, N, s);
-    return launch_tile<E, 128, 192, 2, 2, XT, WT, POST>(a, N, s);
+    if (tune.tgemm_tile >= 0 && tune.tgemm_tile <= 3) tile = tune.tgemm_tile;
+    if (tile == 0) return launch_tile<E, 128, 256, 3, 1, XT, WT, POST>(a, N, tune, s);
+    if (tile == 1) return launch_tile<E, 128, 128, 4, 1, XT, WT, POST>(a, N, tune, s);
+    if (tile == 2) return launch_tile<E, 128, 128, 2, 2, XT, WT, POST>(a, N, tune, s);
+    return launch_tile<E, 128, 192, 2, 2, XT, WT, POST>(a, N, tune, s);
 }
 
 template <typename E>
@@ -477,10 +472,10 @@ hipError_t launch_typed(const TransposedGemm &g, hipStream_t s)
     TGemmArgs<E> a{static_cast<const E *>(g.x), static_cast<const E *>(g.w), static_cast<E *>(g.y),
                    static_cast<const E *>(g.aux), g.rows_valid, g.k_valid, g.Mrows, g.Nout, g.K, g.ldx, g.ldw,
                    g.sx, g.sw, g.sy, 0, 0, 0, g.N};
-    if (g.x_transposed) return launch_shape<E, true, true, 0>(a, g.N, s);
-    if (g.post == 1) return launch_shape<E, false, true, 1>(a, g.N, s);
-    if (g.post == 2) return launch_shape<E, false, true, 2>(a, g.N, s);
-    return launch_shape<E, false, true, 0>(a, g.N, s);
+    if (g.x_transposed) return launch_shape<E, true, true, 0>(a, g.N, g.tune, s);
+    if (g.post == 1) return launch_shape<E, false, true, 1>(a, g.N, g.tune, s);
+    if (g.post == 2) return launch_shape<E, false, true, 2>(a, g.N, g.tune, s);
+    return launch_shape<E, false, true, 0>(a, g.N, g.tune, s);
 }
 
 }  // namespace

@@ -512,8 +512,10 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
 {
     const int n = d.n_groups, m = d.m_local, N = n * m;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
-    // one histogram copy per wave while four of them fit in 48 KB of LDS (N + n <= 3072)
-    const bool per_wave = (size_t)(N + n) * (kRouteBlock / 64) * sizeof(int32_t) <= 48 * 1024;
+    // one histogram copy per wave while four of them fit beside the kernel's static LDS (the probability tile and
+    // its partial sums) in the 64 KB a workgroup may have without opting in: N + n <= 1920
+    constexpr size_t kStaticLds = sizeof(float) * (kRouteBlock * (kColChunk + 1) + 8 * kColChunk);
+    const bool per_wave = (size_t)(N + n) * (kRouteBlock / 64) * sizeof(int32_t) + kStaticLds <= 64 * 1024;
     // the counters' memory is reused for the [4][max(n, m)] partial probability sums
     const size_t counters = (size_t)(N + n) * (per_wave ? kRouteBlock / 64 : 1);
     const size_t lds1 = sizeof(int32_t) * std::max(counters, (size_t)(kRouteBlock / 64) * std::max(n, m));

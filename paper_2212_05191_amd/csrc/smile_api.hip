@@ -105,13 +105,42 @@ smile_status smile_workspace_bytes(const smile_layer_desc *desc, size_t *bytes)
     return SMILE_OK;
 }
 
+// An integer tuning switch from the environment: its value when set to a number in [lo, hi], else -1.
+static int env_switch(const char *name, int lo, int hi)
+{
+    const char *v = std::getenv(name);
+    if (!v || !*v) return -1;
+    char *end = nullptr;
+    const long t = std::strtol(v, &end, 10);
+    return (end && *end == '\0' && t >= lo && t <= hi) ? (int)t : -1;
+}
+
+// The tuning state of a new ctx: the SMILE_* switches as the environment holds them now, and the compute-unit
+// count of the current device (256 when no device answers, e.g. in host-only tests).
+static Tuning read_tuning()
+{
+    Tuning t;
+    t.ffn_tile = env_switch("SMILE_FFN_TILE", 0, 63);
+    t.tgemm_tile = env_switch("SMILE_TGEMM_TILE", 0, 3);
+    t.persist = env_switch("SMILE_FFN_PERSIST", 0, 1);
+    t.router_grad_mfma = env_switch("SMILE_ROUTER_GRAD_MFMA", 0, 1);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        t.cus = cus;
+    else
+        (void)hipGetLastError();
+    return t;
+}
+
 static smile_status make_ctx(const smile_layer_desc *desc, void *workspace, size_t bytes, bool owns, smile_ctx **out)
 {
     smile_ctx *c = new (std::nothrow) smile_ctx;
     if (!c) return SMILE_HIP_ERROR;
     const Layout L = workspace_layout(*desc);
     char *b = static_cast<char *>(workspace);
-    c->desc = *desc;
+    static_cast<smile_layer_desc &>(c->desc) = *desc;
+    c->desc.tune = read_tuning();
     c->base = workspace;
     c->bytes = bytes;
     c->owns = owns;
@@ -290,7 +319,7 @@ smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void 
     // nothing is materialised -- a per-token kernel finishes the routing, builds the slot -> token map
     // and zeroes the rows of dropped tokens; the up GEMM gathers its rows from x through that map and
     // the down GEMM returns gate-weighted rows straight to y.
-    const smile_layer_desc &d = ctx->desc;
+    const LayerDesc &d = ctx->desc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool fused = io->xe == nullptr;
     const LossArgs loss{io->group_count, io->local_count, io->p_sum, io->q_sum, io->loss3};
@@ -429,7 +458,7 @@ smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, f
     if (!std::isfinite(dloss)) return SMILE_BAD_SHAPE;
     const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
     if (st != SMILE_OK) return st;
-    const smile_layer_desc &d = ctx->desc;
+    const LayerDesc &d = ctx->desc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err = launch_combine_backward(d, io->dy, io->ye, io->group_idx, io->local_idx, io->slot, io->gate,
                                              io->dye, io->dgate, s);

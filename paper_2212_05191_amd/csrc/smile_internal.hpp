@@ -221,25 +221,46 @@ struct LiveTileWalk {
     __device__ __forceinline__ void advance() { local += local_step; }
 };
 
+// Tuning overrides and the device's size, fixed when a ctx is created (smile_create reads the SMILE_* environment
+// variables once and asks the runtime for the compute-unit count); -1 = the library's own choice.
+struct Tuning {
+    int ffn_tile = -1;           // SMILE_FFN_TILE: tile shape of the forward expert GEMMs
+    int tgemm_tile = -1;         // SMILE_TGEMM_TILE: tile shape of the gradient GEMMs
+    int persist = -1;            // SMILE_FFN_PERSIST: 0 plain grid, 1 persistent grid
+    int router_grad_mfma = -1;   // SMILE_ROUTER_GRAD_MFMA: 0 keeps the vector-ALU router-gradient kernels
+    int cus = 256;               // compute units of the device the ctx was created on
+};
+
+// the validated layer description of a ctx plus its tuning state
+struct LayerDesc : smile_layer_desc {
+    Tuning tune;
+};
+
 // Workgroup slots of the chip for a kernel of `waves` waves per workgroup that was compiled for `occ` waves per SIMD
-// and uses `lds_bytes` of LDS: 256 CUs x min(register budget, LDS budget).
-constexpr int kCus = 256, kLdsPerCu = 160 * 1024;
-constexpr int workgroup_slots(int waves, int occ, int lds_bytes)
+// and uses `lds_bytes` of LDS: CUs x min(register budget, LDS budget), rounded down to a multiple of the 8 XCDs
+// (the persistent tile walk deals tickets to gridDim / 8 workgroups per XCD).
+constexpr int kLdsPerCu = 160 * 1024;
+constexpr int workgroups_per_cu(int waves, int occ, int lds_bytes)
 {
     const int by_regs = occ * 4 / waves > 0 ? occ * 4 / waves : 1;
     const int by_lds = kLdsPerCu / lds_bytes;
-    return kCus * (by_regs < by_lds ? by_regs : by_lds);
+    return by_regs < by_lds ? by_regs : by_lds;
+}
+inline int workgroup_slots(const Tuning &t, int per_cu)
+{
+    const int slots = (t.cus > 0 ? t.cus : 256) * per_cu / 8 * 8;
+    return slots < 8 ? 8 : slots;
 }
 
 // Persistent launch or the plain grid?  Persistent when the plain grid would be several times the number of slots:
 // then workgroups of empty buffer rows would take turns with the live ones.  With at most a few tiles per slot the
-// two are equal within 1-2 %.  The environment variable SMILE_FFN_PERSIST=0/1 overrides the choice for tuning runs.
-bool use_persistent_grid(int N, long long tiles, int slots);
+// two are equal within 1-2 %.  Tuning::persist overrides the choice.
+bool use_persistent_grid(const Tuning &t, int N, long long tiles, int slots);
 
 }  // namespace smile
 
 struct smile_ctx {
-    smile_layer_desc desc;
+    smile::LayerDesc desc;
     smile::Workspace ws;
     void *base;
     size_t bytes;
@@ -294,12 +315,12 @@ hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32
 // t0/t1: optional events receiving the begin/end timestamps of the up kernel itself (both or neither)
 // x_tokens != nullptr: gather the input rows from the token matrix x[T,d] through ws.slot_token (xe unused)
 // h_save / pre_save (both or neither): write act(.) there instead of ws.hidden, and the pre-activation too
-hipError_t launch_expert_ffn_up(const smile_layer_desc &d, const Workspace &ws, const void *xe,
+hipError_t launch_expert_ffn_up(const LayerDesc &d, const Workspace &ws, const void *xe,
                                 const int32_t *kept_count, const void *w1, const void *b1, hipStream_t s,
                                 hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr, const void *x_tokens = nullptr,
                                 void *h_save = nullptr, void *pre_save = nullptr);
 // y_tokens != nullptr: also write gate[t] * row to y_tokens[t] for the token t of each row (ye may be null)
-hipError_t launch_expert_ffn_down(const smile_layer_desc &d, const Workspace &ws, const int32_t *kept_count,
+hipError_t launch_expert_ffn_down(const LayerDesc &d, const Workspace &ws, const int32_t *kept_count,
                                   const void *w2, const void *b2, void *ye, hipStream_t s,
                                   void *y_tokens = nullptr, const float *gate = nullptr,
                                   const void *h_saved = nullptr);
@@ -318,6 +339,7 @@ struct GroupedGemm {
     const int32_t *x_rows = nullptr;
     const void *aux = nullptr;
     int post = 0;
+    Tuning tune = {};
 };
 hipError_t launch_grouped_gemm_nt(int dtype, const GroupedGemm &g, hipStream_t s);
 
@@ -335,6 +357,7 @@ struct TransposedGemm {
     long long sx, sw, sy;
     bool x_transposed, w_transposed;
     int post;
+    Tuning tune = {};
 };
 hipError_t launch_grouped_gemm_t(int dtype, const TransposedGemm &g, hipStream_t s);
 
@@ -361,10 +384,10 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
                                  const int32_t *local_idx, const float *dgate, const int32_t *group_count,
                                  const int32_t *local_count, float dloss, float *dlp, float *dlq, hipStream_t s);
 // h / pre (both or neither): the hidden activation and pre-activation saved by the forward pass; null: recomputed
-hipError_t launch_expert_ffn_backward(const smile_layer_desc &d, void *workspace, const void *xe,
+hipError_t launch_expert_ffn_backward(const LayerDesc &d, void *workspace, const void *xe,
                                       const int32_t *kept_count, const void *w1, const void *w2, const void *dye,
                                       const void *h, const void *pre, void *dxe, void *dw1, void *dw2, hipStream_t s);
-hipError_t launch_dispatch_backward(const smile_layer_desc &d, const void *dxe, const int32_t *group_idx,
+hipError_t launch_dispatch_backward(const LayerDesc &d, const void *dxe, const int32_t *group_idx,
                                     const int32_t *local_idx, const int32_t *slot, const float *dlp, const float *dlq,
                                     const void *w_inter, const void *w_intra, void *dx, hipStream_t s);
 // bf16 storage and at most 10 chunks of 16 logit columns: the same product on the matrix cores
@@ -378,7 +401,7 @@ bool gate_weights_mfma_applies(const smile_layer_desc &d);
 int gate_weights_mfma_block_tokens(const smile_layer_desc &d, int granule);
 hipError_t launch_gate_weights_mfma(const smile_layer_desc &d, const void *x, const float *dlp, const float *dlq,
                                     float *partial, int blocks, int tokens_per_block, hipStream_t s);
-hipError_t launch_gate_weights_backward(const smile_layer_desc &d, void *workspace, const void *x, const float *dlp,
+hipError_t launch_gate_weights_backward(const LayerDesc &d, void *workspace, const void *x, const float *dlp,
                                         const float *dlq, float *dw_inter, float *dw_intra, hipStream_t s);
 
 // The same for small batches, without the separate scan kernel: every block sums the histogram rows of the
