@@ -148,6 +148,26 @@ smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, cons
                                  int32_t *group_count, int32_t *local_count, int32_t *expert_count,
                                  int32_t *kept_count, float *p_sum, float *q_sum, void *stream);
 
+/* smile_route_bilevel for callers that cannot allocate device memory or create a ctx: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same arguments
+ * and bit-identical results; instead of a ctx it takes the layer description, and its scratch memory
+ * (per-block histograms, partial probability sums, block-local ranks: about 4*(T/256)*(N+2n+2m) +
+ * 8*T bytes) is a fixed array of SMILE_STATIC_SCRATCH_BYTES inside the library's device image, which
+ * every GPU the library runs on holds until the process ends.  Returns SMILE_WORKSPACE when the shape
+ * needs more than that (T = 65536 with 256 experts needs 0.9 MB) and enqueues nothing then.  It calls
+ * no hipMalloc / hipFree and nothing that allocates; the first call on a device looks up the array's
+ * address (make that call outside a graph capture).  All calls on one GPU share the array: calls that
+ * overlap there (other streams, other threads) race, calls in stream order do not, and no call
+ * depends on what an earlier one left in it. */
+#define SMILE_STATIC_SCRATCH_BYTES (4u << 20)
+smile_status smile_route_bilevel_static(const smile_layer_desc *desc, const float *logits_inter,
+                                        const float *logits_intra, const float *bias_inter,
+                                        const float *bias_intra, int32_t *group_idx, int32_t *local_idx,
+                                        int32_t *pos_in_group, int32_t *slot, float *gate, float *p_top,
+                                        float *q_top, int32_t *group_count, int32_t *local_count,
+                                        int32_t *expert_count, int32_t *kept_count, float *p_sum, float *q_sum,
+                                        void *stream);
+
 /* Step 3 -- dispatch: xe[e, slot[t], :] = x[t, :] for every kept token, e =
  * group_idx[t]*m + local_idx[t] (the two routing hops of Section 3.2.1 composed
  * into one row move).  xe[N,C,d] in the ctx dtype; rows at or beyond

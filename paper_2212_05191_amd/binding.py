@@ -51,6 +51,7 @@ class BackwardIO(C.Structure):
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
+    "smile_route_bilevel_static",
     "smile_dispatch", "smile_dispatch_hop1", "smile_dispatch_hop2", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
     "smile_backward_workspace_bytes", "smile_combine_backward", "smile_route_backward", "smile_expert_ffn_backward",
     "smile_dispatch_backward", "smile_gate_weights_backward", "smile_layer_backward",
@@ -79,6 +80,7 @@ def load() -> C.CDLL:
     lib.smile_destroy.argtypes = [vp]
     lib.smile_gate_logits.argtypes = [vp] * 7
     lib.smile_route_bilevel.argtypes = [vp] * 19
+    lib.smile_route_bilevel_static.argtypes = [C.POINTER(LayerDesc)] + [vp] * 18
     lib.smile_dispatch.argtypes = [vp] * 7
     lib.smile_dispatch_hop1.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     lib.smile_dispatch_hop2.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp]
@@ -199,6 +201,18 @@ def smile_route_bilevel(ctx: Ctx, logits_inter, logits_intra, bias_inter, bias_i
                                       _ptr(slot), _ptr(gate), _ptr(p_top), _ptr(q_top), _ptr(group_count),
                                       _ptr(local_count), _ptr(expert_count), _ptr(kept_count), _ptr(p_sum),
                                       _ptr(q_sum), _stream(stream)), "smile_route_bilevel")
+
+
+def smile_route_bilevel_static(desc: LayerDesc, logits_inter, logits_intra, bias_inter, bias_intra, group_idx,
+                               local_idx, pos_in_group, slot, gate, p_top, q_top, group_count, local_count,
+                               expert_count, kept_count, p_sum, q_sum, stream=None):
+    """smile_route_bilevel without a ctx: the scratch memory is a fixed array inside the library."""
+    _check(load().smile_route_bilevel_static(C.byref(desc), _ptr(logits_inter), _ptr(logits_intra),
+                                             _ptr(bias_inter), _ptr(bias_intra), _ptr(group_idx), _ptr(local_idx),
+                                             _ptr(pos_in_group), _ptr(slot), _ptr(gate), _ptr(p_top), _ptr(q_top),
+                                             _ptr(group_count), _ptr(local_count), _ptr(expert_count),
+                                             _ptr(kept_count), _ptr(p_sum), _ptr(q_sum), _stream(stream)),
+           "smile_route_bilevel_static")
 
 
 def smile_dispatch(ctx: Ctx, x, group_idx, local_idx, slot, xe, stream=None):

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsmile.so")
 PEAKS = os.path.join(HERE, "peaks_probe")
 SOURCES = ["smile_api.hip", "gate_logits.hip", "route.hip", "permute.hip", "expert_ffn.hip", "aux_loss.hip",
-           "backward.hip", "gemm_transposed.hip", "router_grad_mfma.hip"]
+           "backward.hip", "gemm_transposed.hip", "router_grad_mfma.hip", "static_scratch.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

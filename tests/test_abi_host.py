@@ -214,3 +214,25 @@ def test_binding_raises_with_status():
     with pytest.raises(B.SmileError) as ei:
         B.smile_workspace_bytes(_desc(T=-5))
     assert ei.value.status == B.BAD_SHAPE
+
+
+def test_static_scratch_routing_rejects_before_any_launch():
+    """smile_route_bilevel_static checks the description, the pointers and the size of its fixed scratch
+    array on the host before it looks up that array or enqueues anything (so this needs no GPU)."""
+    lib = B.load()
+    p = 0x7F0000000000 + 4096
+    args = [p] * 17
+    assert lib.smile_route_bilevel_static(None, *args, None) == B.INVALID_ARG
+    assert lib.smile_route_bilevel_static(C.byref(_desc(T=0)), *args, None) == B.BAD_SHAPE
+    assert lib.smile_route_bilevel_static(C.byref(_desc(dtype=7)), *args, None) == B.UNSUPPORTED
+    for i in [0, 1, 4, 7, 16]:
+        bad = list(args)
+        bad[i] = None
+        assert lib.smile_route_bilevel_static(C.byref(_desc()), *bad, None) == B.INVALID_ARG
+    bad = list(args)
+    bad[5] = p + 4
+    assert lib.smile_route_bilevel_static(C.byref(_desc()), *bad, None) == B.INVALID_ARG
+    # routing scratch beyond the fixed array: 16384 blocks x 256 experts x 4 bytes alone is 16 MiB
+    huge = _desc(T=1 << 22, n_groups=32, m_local=8, capacity=20000)
+    assert lib.smile_validate_desc(C.byref(huge)) == B.OK
+    assert lib.smile_route_bilevel_static(C.byref(huge), *args, None) == B.WORKSPACE
