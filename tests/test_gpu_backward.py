@@ -18,8 +18,8 @@ import parity  # noqa: E402
 from parity import normwise  # noqa: E402
 
 ALPHA, BETA = 0.005, 0.005
-# fp32 sums of up to T products against fp64: far below these; bf16 tensors carry one or two roundings
-TOL_F32_SUM = 2e-5
+# fp32 sums of up to T products against fp64 (measured: 3e-7 and below); bf16 tensors carry one or two roundings
+TOL_F32_SUM = 1e-5
 
 
 def _say(msg):
@@ -54,18 +54,31 @@ def _forward_backward(cfg, chained=False, dloss=1.0, **kw):
     return layer
 
 
-def _fetch_backward(layer):
+class _LazyExperts:
+    """A per-expert gradient tensor [N, ...] left on the device: indexing by expert copies that expert only (the
+    weight gradients of a 256-expert configuration are 8 GB as host float32)."""
+
+    def __init__(self, t):
+        self.t = t
+
+    def __getitem__(self, e):
+        from paper_2212_05191_amd.runner import to_host
+        return to_host(self.t[e])
+
+
+def _fetch_backward(layer, lazy_weight_grads=False):
     import torch
     from paper_2212_05191_amd.runner import to_host
     torch.cuda.synchronize()
-    return {k: to_host(v) for k, v in layer.bwd.__dict__.items()}
+    return {k: (_LazyExperts(v) if lazy_weight_grads and k in ("dw1", "dw2") else to_host(v))
+            for k, v in layer.bwd.__dict__.items()}
 
 
 def _check_steps(cfg, layer, dloss=1.0, experts=None):
     """experts: None = compare the expert FFN step on every expert, else on the listed ones."""
     tol = parity.TOL[cfg.dtype]
     fwd = parity.fetch(layer)
-    out = _fetch_backward(layer)
+    out = _fetch_backward(layer, lazy_weight_grads=experts is not None)
     x, wi, wq, bi, bq = parity.host_inputs(cfg)
     dy = wl.gen_output_grad(cfg)
     n, m, N, Cap = cfg.n_groups, cfg.m_local, cfg.N, cfg.capacity
@@ -120,7 +133,7 @@ def _check_steps(cfg, layer, dloss=1.0, experts=None):
 def _check_end_to_end(cfg, fwd, out, dloss=1.0):
     """The final gradients against the oracle's own chain (forward from the GPU's logits, so that the routing
     decisions are the same; everything after that is the oracle's)."""
-    tol = 2 * parity.TOL[cfg.dtype]
+    tol = parity.TOL[cfg.dtype]
     x, wi, wq, bi, bq = parity.host_inputs(cfg)
     w1 = np.stack([wl.gen_expert_weights(cfg, e)[0] for e in range(cfg.N)])
     w2 = np.stack([wl.gen_expert_weights(cfg, e)[1] for e in range(cfg.N)])
@@ -305,15 +318,20 @@ def test_backward_large_aux_coefficients(torch_cuda):
         layer.close()
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
 def test_backward_full_size_sampled(torch_cuda, name):
-    """Benchmark configurations at full size: every streaming / router step completely, the expert FFN step on
-    the first, last, fullest and emptiest expert."""
+    """Benchmark configurations at full size: every streaming / router step completely, the expert FFN step
+    (every element of dxe, dw1 and dw2 of the expert) on the first, last, fullest and emptiest expert and on
+    eight more drawn at random."""
     cfg = wl.CONFIGS[name]
     layer = _forward_backward(cfg, chained=True, workers=16)
     try:
-        kept = parity.fetch(layer)["kept_count"]
-        picks = sorted({0, cfg.N - 1, int(np.argmax(kept)), int(np.argmin(kept))})
+        import torch
+        torch.cuda.synchronize()
+        kept = layer.buf.kept_count.cpu().numpy()
+        picks = {0, cfg.N - 1, int(np.argmax(kept)), int(np.argmin(kept))}
+        picks |= set(int(e) for e in np.random.default_rng(7).choice(cfg.N, size=min(8, cfg.N), replace=False))
+        picks = sorted(picks)
         _, _, info = _check_steps(cfg, layer, experts=picks)
         _say(f"   {({k: float(f'{v:.2e}') for k, v in info.items()})}")
     finally:
