@@ -114,6 +114,19 @@ smile_status smile_create_with_workspace(const smile_layer_desc *desc, void *wor
  * must have synchronised every stream that used it.  NULL is allowed. */
 smile_status smile_destroy(smile_ctx *ctx);
 
+/* Kernel timing, for benchmarks and profiles.  `events` is an array of 2*pairs hipEvent_t handles
+ * (passed as void*, created by the caller with timing enabled, owned by the caller and alive until
+ * detached).  While attached, every kernel that a later call on this ctx launches takes the next pair
+ * (start, stop), which receives the begin and end timestamps of that kernel itself, so that
+ * hipEventElapsedTime(start, stop) after synchronisation is the kernel's own duration without launch
+ * gaps.  Each call starts again at pair 0; kernels beyond `pairs` (at most 32 are used) run untimed.
+ * pairs = 0 detaches.  smile_kernel_timing_count: kernels that took a pair in the most recent call;
+ * smile_kernel_timing_name: the kernel's name (a static string, "" out of range).  Results are
+ * unchanged.  The array must not be in use by two threads at once. */
+smile_status smile_kernel_timing(smile_ctx *ctx, void **events, int32_t pairs);
+int32_t smile_kernel_timing_count(const smile_ctx *ctx);
+const char *smile_kernel_timing_name(const smile_ctx *ctx, int32_t i);
+
 /* Step 1 -- router logits r(x) = W_r x (Section 2, text before Eq. 1) for the
  * two tied routers of Section 3.2.1, both reading the same token vector:
  *   logits_inter[t,i] = sum_k x[t,k] * w_inter[i,k]      [T,n] fp32

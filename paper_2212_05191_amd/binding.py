@@ -51,7 +51,7 @@ class BackwardIO(C.Structure):
 EXPORTS = (
     "smile_status_string", "smile_version", "smile_capacity", "smile_validate_desc", "smile_workspace_bytes",
     "smile_create", "smile_create_with_workspace", "smile_destroy", "smile_gate_logits", "smile_route_bilevel",
-    "smile_route_bilevel_static",
+    "smile_route_bilevel_static", "smile_kernel_timing", "smile_kernel_timing_count", "smile_kernel_timing_name",
     "smile_dispatch", "smile_dispatch_hop1", "smile_dispatch_hop2", "smile_expert_ffn", "smile_expert_ffn_up", "smile_expert_ffn_down", "smile_expert_ffn_up_timed", "smile_combine", "smile_aux_loss", "smile_layer_forward",
     "smile_backward_workspace_bytes", "smile_combine_backward", "smile_route_backward", "smile_expert_ffn_backward",
     "smile_dispatch_backward", "smile_gate_weights_backward", "smile_layer_backward",
@@ -79,6 +79,10 @@ def load() -> C.CDLL:
     lib.smile_create_with_workspace.argtypes = [C.POINTER(LayerDesc), vp, C.c_size_t, C.POINTER(vp)]
     lib.smile_destroy.argtypes = [vp]
     lib.smile_gate_logits.argtypes = [vp] * 7
+    lib.smile_kernel_timing.argtypes = [vp, C.POINTER(vp), i32]
+    lib.smile_kernel_timing_count.argtypes = [vp]
+    lib.smile_kernel_timing_count.restype = i32
+    lib.smile_kernel_timing_name.argtypes = [vp, i32]
     lib.smile_route_bilevel.argtypes = [vp] * 19
     lib.smile_route_bilevel_static.argtypes = [C.POINTER(LayerDesc)] + [vp] * 18
     lib.smile_dispatch.argtypes = [vp] * 7
@@ -100,6 +104,7 @@ def load() -> C.CDLL:
     lib.smile_layer_backward.argtypes = [vp, C.POINTER(BackwardIO), C.c_float, vp, C.c_size_t, vp]
     for name in EXPORTS[3:]:
         getattr(lib, name).restype = i32
+    lib.smile_kernel_timing_name.restype = C.c_char_p
     _lib = lib
     return lib
 

@@ -34,15 +34,18 @@ def _run(cmd, verbose):
         print(out)
 
 
-def build(verbose: bool = False, jobs: int | None = None) -> str:
-    """Compile every source (always: no staleness check) and link the library and the peak-rate probe."""
+def build(verbose: bool = False, jobs: int | None = None, only: list[str] | None = None) -> str:
+    """Compile every source (always: no staleness check) and link the library and the peak-rate probe.
+    only: recompile just these sources (the other objects must exist from an earlier full build) and relink."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
-    cmds = [[hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    cmds = [[hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)
+            if only is None or s in only]
     # the stand-alone microbenchmark of the chip's measured peak rates (no library code in it)
-    cmds.append([hipcc, *FLAGS, os.path.join(CSRC, "peaks_probe.hip"), "-o", PEAKS])
+    if only is None or "peaks_probe.hip" in only:
+        cmds.append([hipcc, *FLAGS, os.path.join(CSRC, "peaks_probe.hip"), "-o", PEAKS])
     jobs = jobs or min(len(cmds), max(1, min(16, os.cpu_count() or 1)))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
@@ -51,5 +54,5 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, only=sys.argv[1:] or None))
     sys.exit(0)

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(64) void aux_loss_kernel(
 hipError_t launch_aux_loss(const smile_layer_desc &d, const int32_t *group_count, const int32_t *local_count,
                            const float *p_sum, const float *q_sum, float *out3, hipStream_t s)
 {
-    hipLaunchKernelGGL(aux_loss_kernel, dim3(1), dim3(64), 0, s, group_count, local_count, p_sum, q_sum, d.T,
+    SMILE_LAUNCH(aux_loss_kernel, dim3(1), dim3(64), 0, s, group_count, local_count, p_sum, q_sum, d.T,
                        d.n_groups, d.m_local, d.alpha, d.beta, out3);
     return hipGetLastError();
 }

@@ -242,7 +242,7 @@ hipError_t launch_transpose(const void *in, void *out, const int32_t *kept, int 
                             hipStream_t s)
 {
     const int row_tiles = (rows_out + 63) / 64, col_tiles = (cols + 63) / 64;
-    hipLaunchKernelGGL((transpose_pad_kernel<E, VEC>), dim3((unsigned)((size_t)N * row_tiles * col_tiles)),
+    SMILE_LAUNCH((transpose_pad_kernel<E, VEC>), dim3((unsigned)((size_t)N * row_tiles * col_tiles)),
                        dim3(kThreads), 0, s, static_cast<const E *>(in), static_cast<E *>(out), kept, R, cols,
                        rows_out, row_tiles, col_tiles);
     return hipGetLastError();
@@ -453,7 +453,7 @@ hipError_t launch_combine_backward(const smile_layer_desc &d, const void *dy, co
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_DTYPE_SWITCH(d.dtype, SMILE_BWD_LPR_SWITCH(
-        lpr, hipLaunchKernelGGL((combine_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dy),
+        lpr, SMILE_LAUNCH((combine_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dy),
                                 static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,
                                 static_cast<u32x4 *>(dye), dgate, d.T, ppr, d.m_local, d.capacity)));
     return hipGetLastError();
@@ -473,12 +473,12 @@ hipError_t launch_route_backward(const smile_layer_desc &d, const float *logits_
     int tokens = kThreads;
     while (tokens >= 64 && tokens * row_bytes > 64 * 1024) tokens /= 2;
     if (tokens >= 64 && d.n_groups + d.m_local >= 32) {   // narrower routers: measured faster from memory
-        hipLaunchKernelGGL(route_backward_tiled_kernel, dim3((d.T + tokens - 1) / tokens), dim3(kThreads),
+        SMILE_LAUNCH(route_backward_tiled_kernel, dim3((d.T + tokens - 1) / tokens), dim3(kThreads),
                            tokens * row_bytes, s, logits_inter, logits_intra, bias_inter, bias_intra, group_idx, local_idx,
                            dgate, group_count, local_count, d.T, d.n_groups, d.m_local, ci, cq, dlp, dlq, tokens);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(route_backward_kernel, dim3((d.T + kThreads - 1) / kThreads), dim3(kThreads), 0, s, logits_inter,
+    SMILE_LAUNCH(route_backward_kernel, dim3((d.T + kThreads - 1) / kThreads), dim3(kThreads), 0, s, logits_inter,
                        logits_intra, bias_inter, bias_intra, group_idx, local_idx, dgate, group_count, local_count, d.T,
                        d.n_groups, d.m_local, ci, cq, dlp, dlq);
     return hipGetLastError();
@@ -559,7 +559,7 @@ hipError_t launch_dispatch_backward(const LayerDesc &d, const void *dxe, const i
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
     SMILE_DTYPE_SWITCH(d.dtype, SMILE_BWD_LPR_SWITCH(
-        lpr, hipLaunchKernelGGL((dispatch_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dxe),
+        lpr, SMILE_LAUNCH((dispatch_backward_kernel<DT, L>), grid, block, 0, s, static_cast<const u32x4 *>(dxe),
                                 group_idx, local_idx, slot, dlp, dlq, static_cast<const u32x4 *>(w_inter),
                                 static_cast<const u32x4 *>(w_intra), static_cast<u32x4 *>(dx), d.T, ppr, d.n_groups,
                                 d.m_local, d.capacity)));
@@ -579,13 +579,13 @@ hipError_t launch_gate_weights_backward(const LayerDesc &d, void *workspace, con
         err = launch_gate_weights_mfma(d, x, dlp, dlq, partial, blocks, tokens, s);
     } else {
         const dim3 grid(L.gw_blocks, (d.d_model + kGwCols - 1) / kGwCols), block(kThreads);
-        SMILE_DTYPE_SWITCH(d.dtype, hipLaunchKernelGGL(gate_weights_partial_kernel<DT>, grid, block, 0, s, x, dlp, dlq,
+        SMILE_DTYPE_SWITCH(d.dtype, SMILE_LAUNCH(gate_weights_partial_kernel<DT>, grid, block, 0, s, x, dlp, dlq,
                                                        partial, d.T, d.d_model, d.n_groups, d.m_local));
         err = hipGetLastError();
     }
     if (err != hipSuccess) return err;
     const long long total = (long long)(d.n_groups + d.m_local) * d.d_model;
-    hipLaunchKernelGGL(gate_weights_reduce_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
+    SMILE_LAUNCH(gate_weights_reduce_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
                        partial, dw_inter, dw_intra, blocks, d.d_model, d.n_groups, d.m_local);
     return hipGetLastError();
 }

@@ -132,12 +132,12 @@ void launch_half_rt(const smile_layer_desc &d, const void *x, const void *w_inte
 {
     const int blocks = (d.T + kRows * RT - 1) / (kRows * RT);
     if (d.dtype == SMILE_DTYPE_BF16)
-        hipLaunchKernelGGL((gate_logits_half_kernel<__bf16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
+        SMILE_LAUNCH((gate_logits_half_kernel<__bf16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
                            static_cast<const __bf16 *>(x), static_cast<const __bf16 *>(w_inter),
                            static_cast<const __bf16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
                            d.n_groups, d.m_local, col0);
     else
-        hipLaunchKernelGGL((gate_logits_half_kernel<_Float16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
+        SMILE_LAUNCH((gate_logits_half_kernel<_Float16, CT, RT>), dim3(blocks), dim3(64 * kWaves), 0, s,
                            static_cast<const _Float16 *>(x), static_cast<const _Float16 *>(w_inter),
                            static_cast<const _Float16 *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
                            d.n_groups, d.m_local, col0);
@@ -177,7 +177,7 @@ hipError_t launch_gate_logits(const smile_layer_desc &d, const void *x, const vo
         }
     } else {
         const long long total = (long long)d.T * cols;
-        hipLaunchKernelGGL(gate_logits_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+        SMILE_LAUNCH(gate_logits_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                            static_cast<const float *>(x), static_cast<const float *>(w_inter),
                            static_cast<const float *>(w_intra), logits_inter, logits_intra, d.T, d.d_model,
                            d.n_groups, d.m_local);

@@ -437,11 +437,11 @@ hipError_t launch_tile(TGemmArgs<E> a, int N, const Tuning &tune, hipStream_t s)
     a.N = N;
     const int slots = workgroup_slots(tune, workgroups_per_cu(4, OCC, STAGES * (BM + BN) * BK * 2));
     if (use_persistent_grid(tune, N, a.tiles, slots)) {
-        hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST, true>), dim3(slots), dim3(256),
+        SMILE_LAUNCH((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST, true>), dim3(slots), dim3(256),
                            0, s, a);
     } else {
         const int per_xcd = (a.tiles + kXcds - 1) / kXcds;
-        hipLaunchKernelGGL((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
+        SMILE_LAUNCH((grouped_gemm_t_kernel<E, BM, BN, 2, 2, STAGES, OCC, XT, WT, POST>), dim3(per_xcd * kXcds),
                            dim3(256), 0, s, a);
     }
     return hipGetLastError();

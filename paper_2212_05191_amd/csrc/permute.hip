@@ -316,7 +316,7 @@ hipError_t launch_dispatch(const smile_layer_desc &d, const void *x, const int32
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
+    SMILE_LPR_SWITCH(lpr, SMILE_LAUNCH(dispatch_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
                                              group_idx, local_idx, slot, static_cast<u32x4 *>(xe), d.T, ppr, d.m_local,
                                              d.capacity));
     return hipGetLastError();
@@ -328,7 +328,7 @@ hipError_t launch_dispatch_hop1(const smile_layer_desc &d, const void *x, const 
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop1_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
+    SMILE_LPR_SWITCH(lpr, SMILE_LAUNCH(dispatch_hop1_kernel<L>, grid, block, 0, s, static_cast<const u32x4 *>(x),
                                              group_idx, pos_in_group, static_cast<u32x4 *>(xg), d.T, ppr, group_rows));
     return hipGetLastError();
 }
@@ -340,7 +340,7 @@ hipError_t launch_dispatch_hop2(const smile_layer_desc &d, const void *xg, const
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_hop2_kernel<L>, grid, block, 0, s,
+    SMILE_LPR_SWITCH(lpr, SMILE_LAUNCH(dispatch_hop2_kernel<L>, grid, block, 0, s,
                                              static_cast<const u32x4 *>(xg), group_idx, local_idx, pos_in_group, slot,
                                              static_cast<u32x4 *>(xe), d.T, ppr, d.m_local, d.capacity, group_rows));
     return hipGetLastError();
@@ -353,7 +353,7 @@ hipError_t launch_dispatch_finalize(const smile_layer_desc &d, const Workspace &
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
-    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL(dispatch_finalize_kernel<L>, grid, block, 0, s,
+    SMILE_LPR_SWITCH(lpr, SMILE_LAUNCH(dispatch_finalize_kernel<L>, grid, block, 0, s,
                                              static_cast<const u32x4 *>(x), group_idx, local_idx, ws.block_expert_hist,
                                              ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group, slot,
                                              static_cast<u32x4 *>(xe), ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr,
@@ -367,7 +367,7 @@ hipError_t launch_finalize_map(const smile_layer_desc &d, const Workspace &ws, c
 {
     const int ppr = d.d_model * elem_size(d.dtype) / 16;
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
-    hipLaunchKernelGGL(finalize_map_kernel, dim3(B), dim3(kRouteBlock), 0, s, group_idx, local_idx,
+    SMILE_LAUNCH(finalize_map_kernel, dim3(B), dim3(kRouteBlock), 0, s, group_idx, local_idx,
                        ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block, pos_in_group,
                        slot, ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr, d.n_groups, d.m_local, d.capacity, loss,
                        d.alpha, d.beta);
@@ -383,7 +383,7 @@ hipError_t launch_finalize_map_scan(const smile_layer_desc &d, const Workspace &
     const int B = (d.T + kRouteBlock - 1) / kRouteBlock;
     const int n = d.n_groups, m = d.m_local;
     const size_t lds = sizeof(int32_t) * (size_t)(n * m + n + 2 * (n + m));
-    hipLaunchKernelGGL(finalize_map_scan_kernel, dim3(B), dim3(kRouteBlock), lds, s, group_idx, local_idx,
+    SMILE_LAUNCH(finalize_map_scan_kernel, dim3(B), dim3(kRouteBlock), lds, s, group_idx, local_idx,
                        ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum, ws.rank_in_block,
                        ws.pos_in_block, pos_in_group, slot, ws.slot_token, static_cast<u32x4 *>(y), d.T, ppr, n, m,
                        d.capacity, group_count, local_count, expert_count, kept_count, p_sum, q_sum, loss3, d.alpha,
@@ -398,7 +398,7 @@ hipError_t launch_combine(const smile_layer_desc &d, const void *ye, const int32
     const int lpr = lanes_per_row(ppr);
     const dim3 grid((d.T + kThreads / lpr - 1) / (kThreads / lpr)), block(kThreads);
 #define SMILE_COMBINE(DT)                                                                                          \
-    SMILE_LPR_SWITCH(lpr, hipLaunchKernelGGL((combine_kernel<DT, L>), grid, block, 0, s,                             \
+    SMILE_LPR_SWITCH(lpr, SMILE_LAUNCH((combine_kernel<DT, L>), grid, block, 0, s,                             \
                                              static_cast<const u32x4 *>(ye), group_idx, local_idx, slot, gate,       \
                                              static_cast<u32x4 *>(y), d.T, ppr, d.m_local, d.capacity))
     if (d.dtype == SMILE_DTYPE_BF16) { SMILE_COMBINE(SMILE_DTYPE_BF16); }

@@ -521,7 +521,7 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
     const size_t lds1 = sizeof(int32_t) * std::max(counters, (size_t)(kRouteBlock / 64) * std::max(n, m));
     const int cp = n <= 8 ? 8 : (n <= 32 ? 32 : 0), cq = m <= 8 ? 8 : (m <= 32 ? 32 : 0);
 #define SMILE_DECIDE(PW, CP, CQ)                                                                                     \
-    hipLaunchKernelGGL((route_decide_kernel<PW, CP, CQ>), dim3(B), dim3(kRouteBlock), lds1, s, logits_inter,          \
+    SMILE_LAUNCH((route_decide_kernel<PW, CP, CQ>), dim3(B), dim3(kRouteBlock), lds1, s, logits_inter,          \
                        logits_intra, bias_inter, bias_intra, d.T, n, m, ceil_log2(n), ceil_log2(N), group_idx,        \
                        local_idx, ws.pos_in_block, ws.rank_in_block, gate, p_top, q_top, ws.block_expert_hist,         \
                        ws.block_group_hist, ws.block_p_sum, ws.block_q_sum)
@@ -535,24 +535,24 @@ hipError_t launch_route(const smile_layer_desc &d, const Workspace &ws, const fl
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !scan) return err;   // !scan: the caller's last step scans the histograms itself
     const int columns = N + 2 * n + 2 * m;
-    hipLaunchKernelGGL(route_scan_kernel, dim3((columns + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0, s, B, n,
+    SMILE_LAUNCH(route_scan_kernel, dim3((columns + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0, s, B, n,
                        m, d.capacity, ws.block_expert_hist, ws.block_group_hist, ws.block_p_sum, ws.block_q_sum,
                        group_count, local_count, expert_count, kept_count, p_sum, q_sum);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (d.group_capacity > 0) {
-        hipLaunchKernelGGL(route_first_hop_kernel, dim3(B), dim3(kRouteBlock), sizeof(int32_t) * (size_t)N, s, d.T, n, m,
+        SMILE_LAUNCH(route_first_hop_kernel, dim3(B), dim3(kRouteBlock), sizeof(int32_t) * (size_t)N, s, d.T, n, m,
                            d.group_capacity, ceil_log2(N), group_idx, local_idx, ws.block_group_hist, ws.pos_in_block,
                            ws.rank_in_block, ws.block_expert_hist);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(route_scan_experts_kernel, dim3((N + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0,
+        SMILE_LAUNCH(route_scan_experts_kernel, dim3((N + kScanWaves - 1) / kScanWaves), dim3(64 * kScanWaves), 0,
                            s, B, N, d.capacity, ws.block_expert_hist, kept_count);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
     if (!finalize) return err;
-    hipLaunchKernelGGL(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,
+    SMILE_LAUNCH(route_finalize_kernel, dim3(B), dim3(kRouteBlock), 0, s, d.T, n, m, d.capacity, group_idx,
                        local_idx, ws.block_expert_hist, ws.block_group_hist, ws.rank_in_block, ws.pos_in_block,
                        pos_in_group, slot);
     return hipGetLastError();

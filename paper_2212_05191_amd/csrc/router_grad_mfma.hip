@@ -170,7 +170,7 @@ hipError_t launch_dx(const smile_layer_desc &d, const void *dxe, const int32_t *
                      void *dx, int kp, hipStream_t s)
 {
     const dim3 grid((d.T + kDxTokens - 1) / kDxTokens, (d.d_model + dx_cols(KC) - 1) / dx_cols(KC)), block(kThreads);
-    hipLaunchKernelGGL(dispatch_backward_mfma_kernel<KC>, grid, block, 0, s, static_cast<const __bf16 *>(dxe), group_idx,
+    SMILE_LAUNCH(dispatch_backward_mfma_kernel<KC>, grid, block, 0, s, static_cast<const __bf16 *>(dxe), group_idx,
                        local_idx, slot, dlp, dlq, static_cast<const __bf16 *>(w_inter),
                        static_cast<const __bf16 *>(w_intra), static_cast<__bf16 *>(dx), d.T, d.d_model, d.n_groups,
                        d.m_local, d.capacity, kp);
@@ -323,7 +323,7 @@ hipError_t launch_gw(const smile_layer_desc &d, const void *x, const float *dlp,
                      int blocks, int tokens_per_block, hipStream_t s)
 {
     const dim3 grid(blocks, (d.d_model + kGwCb - 1) / kGwCb), block(kThreads);
-    hipLaunchKernelGGL(gate_weights_mfma_kernel<RT>, grid, block, 0, s, static_cast<const __bf16 *>(x), dlp, dlq, partial,
+    SMILE_LAUNCH(gate_weights_mfma_kernel<RT>, grid, block, 0, s, static_cast<const __bf16 *>(x), dlp, dlq, partial,
                        d.T, d.d_model, d.n_groups, d.m_local, tokens_per_block);
     return hipGetLastError();
 }

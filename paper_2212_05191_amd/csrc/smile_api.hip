@@ -8,6 +8,27 @@
 
 namespace smile {
 
+thread_local KernelTimer *tls_kernel_timer = nullptr;
+
+// Installs the ctx's kernel timer (if events are attached) for the duration of one library call on this thread.
+// A call made from inside another library call (smile_expert_ffn calls its two halves) leaves the outer one's
+// state alone.
+struct TimerScope {
+    bool mine = false;
+    explicit TimerScope(smile_ctx *c)
+    {
+        if (c && c->timer.pairs > 0 && !tls_kernel_timer) {
+            c->timer.used = 0;
+            tls_kernel_timer = &c->timer;
+            mine = true;
+        }
+    }
+    ~TimerScope()
+    {
+        if (mine) tls_kernel_timer = nullptr;
+    }
+};
+
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 Layout workspace_layout(const smile_layer_desc &d)
@@ -120,7 +141,7 @@ static int env_switch(const char *name, int lo, int hi)
 static Tuning read_tuning()
 {
     Tuning t;
-    t.ffn_tile = env_switch("SMILE_FFN_TILE", 0, 63);
+    t.ffn_tile = env_switch("SMILE_FFN_TILE", 0, 6);
     t.tgemm_tile = env_switch("SMILE_TGEMM_TILE", 0, 3);
     t.persist = env_switch("SMILE_FFN_PERSIST", 0, 1);
     t.router_grad_mfma = env_switch("SMILE_ROUTER_GRAD_MFMA", 0, 1);
@@ -191,9 +212,29 @@ smile_status smile_destroy(smile_ctx *ctx)
     return st;
 }
 
+smile_status smile_kernel_timing(smile_ctx *ctx, void **events, int32_t pairs)
+{
+    if (!ctx || pairs < 0 || (pairs > 0 && !events)) return SMILE_INVALID_ARG;
+    if (pairs > kMaxTimedKernels) pairs = kMaxTimedKernels;
+    for (int32_t i = 0; i < 2 * pairs; ++i)
+        if (!events[i]) return SMILE_INVALID_ARG;
+    ctx->timer.events = pairs ? reinterpret_cast<hipEvent_t *>(events) : nullptr;
+    ctx->timer.pairs = pairs;
+    ctx->timer.used = 0;
+    return SMILE_OK;
+}
+
+int32_t smile_kernel_timing_count(const smile_ctx *ctx) { return ctx ? ctx->timer.used : 0; }
+
+const char *smile_kernel_timing_name(const smile_ctx *ctx, int32_t i)
+{
+    return (ctx && i >= 0 && i < ctx->timer.used && ctx->timer.names[i]) ? ctx->timer.names[i] : "";
+}
+
 smile_status smile_gate_logits(smile_ctx *ctx, const void *x, const void *w_inter, const void *w_intra,
                                float *logits_inter, float *logits_intra, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(x) || bad(w_inter) || bad(w_intra) || bad(logits_inter) || bad(logits_intra))
         return SMILE_INVALID_ARG;
     return from_hip(launch_gate_logits(ctx->desc, x, w_inter, w_intra, logits_inter, logits_intra,
@@ -207,6 +248,7 @@ smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, cons
                                  int32_t *group_count, int32_t *local_count, int32_t *expert_count,
                                  int32_t *kept_count, float *p_sum, float *q_sum, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(logits_inter) || bad(logits_intra) || bad_opt(bias_inter) || bad_opt(bias_intra) ||
         bad(group_idx) || bad(local_idx) || bad(pos_in_group) || bad(slot) || bad(gate) || bad(p_top) ||
         bad(q_top) || bad(group_count) || bad(local_count) || bad(expert_count) || bad(kept_count) ||
@@ -221,6 +263,7 @@ smile_status smile_route_bilevel(smile_ctx *ctx, const float *logits_inter, cons
 smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_idx, const int32_t *local_idx,
                             const int32_t *slot, void *xe, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(x) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(xe)) return SMILE_INVALID_ARG;
     return from_hip(launch_dispatch(ctx->desc, x, group_idx, local_idx, slot, xe, static_cast<hipStream_t>(stream)));
 }
@@ -228,6 +271,7 @@ smile_status smile_dispatch(smile_ctx *ctx, const void *x, const int32_t *group_
 smile_status smile_dispatch_hop1(smile_ctx *ctx, const void *x, const int32_t *group_idx,
                                  const int32_t *pos_in_group, int32_t group_rows, void *xg, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(x) || bad(group_idx) || bad(pos_in_group) || bad(xg)) return SMILE_INVALID_ARG;
     if (group_rows < 1 || (int64_t)group_rows * ctx->desc.n_groups >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
     return from_hip(launch_dispatch_hop1(ctx->desc, x, group_idx, pos_in_group, group_rows, xg,
@@ -238,6 +282,7 @@ smile_status smile_dispatch_hop2(smile_ctx *ctx, const void *xg, const int32_t *
                                  const int32_t *local_idx, const int32_t *pos_in_group, const int32_t *slot,
                                  int32_t group_rows, void *xe, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(xg) || bad(group_idx) || bad(local_idx) || bad(pos_in_group) || bad(slot) || bad(xe))
         return SMILE_INVALID_ARG;
     if (group_rows < 1 || (int64_t)group_rows * ctx->desc.n_groups >= (int64_t)1 << 31) return SMILE_BAD_SHAPE;
@@ -248,6 +293,7 @@ smile_status smile_dispatch_hop2(smile_ctx *ctx, const void *xg, const int32_t *
 smile_status smile_expert_ffn_up(smile_ctx *ctx, const void *xe, const int32_t *kept_count,
                                  const void *w1, const void *b1, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1)) return SMILE_INVALID_ARG;
     return from_hip(launch_expert_ffn_up(ctx->desc, ctx->ws, xe, kept_count, w1, b1, static_cast<hipStream_t>(stream)));
 }
@@ -256,6 +302,7 @@ smile_status smile_expert_ffn_up_timed(smile_ctx *ctx, const void *xe, const int
                                        const void *w1, const void *b1, void *start_event, void *stop_event,
                                        void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1) || !start_event || !stop_event)
         return SMILE_INVALID_ARG;
     return from_hip(launch_expert_ffn_up(ctx->desc, ctx->ws, xe, kept_count, w1, b1, static_cast<hipStream_t>(stream),
@@ -265,6 +312,7 @@ smile_status smile_expert_ffn_up_timed(smile_ctx *ctx, const void *xe, const int
 smile_status smile_expert_ffn_down(smile_ctx *ctx, const int32_t *kept_count, const void *w2, const void *b2,
                                    void *ye, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(kept_count) || bad(w2) || bad_opt(b2) || bad(ye)) return SMILE_INVALID_ARG;
     return from_hip(launch_expert_ffn_down(ctx->desc, ctx->ws, kept_count, w2, b2, ye, static_cast<hipStream_t>(stream)));
 }
@@ -273,6 +321,7 @@ smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kep
                               const void *w1, const void *b1, const void *w2, const void *b2,
                               void *ye, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad_opt(b1) || bad(w2) || bad_opt(b2) || bad(ye))
         return SMILE_INVALID_ARG;
     smile_status st = smile_expert_ffn_up(ctx, xe, kept_count, w1, b1, stream);
@@ -283,6 +332,7 @@ smile_status smile_expert_ffn(smile_ctx *ctx, const void *xe, const int32_t *kep
 smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_idx, const int32_t *local_idx,
                            const int32_t *slot, const float *gate, void *y, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(ye) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(gate) || bad(y))
         return SMILE_INVALID_ARG;
     return from_hip(launch_combine(ctx->desc, ye, group_idx, local_idx, slot, gate, y,
@@ -292,6 +342,7 @@ smile_status smile_combine(smile_ctx *ctx, const void *ye, const int32_t *group_
 smile_status smile_aux_loss(smile_ctx *ctx, const int32_t *group_count, const int32_t *local_count,
                             const float *p_sum, const float *q_sum, float *out3, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(group_count) || bad(local_count) || bad(p_sum) || bad(q_sum) || bad(out3))
         return SMILE_INVALID_ARG;
     return from_hip(launch_aux_loss(ctx->desc, group_count, local_count, p_sum, q_sum, out3,
@@ -300,6 +351,7 @@ smile_status smile_aux_loss(smile_ctx *ctx, const int32_t *group_count, const in
 
 smile_status smile_layer_forward(smile_ctx *ctx, const smile_layer_io *io, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || !io) return SMILE_INVALID_ARG;
     // check every pointer first so that a bad argument of a late step leaves nothing enqueued
     if (bad(io->x) || bad(io->w_inter) || bad(io->w_intra) || bad(io->w1) || bad_opt(io->b1) || bad(io->w2) ||
@@ -384,6 +436,7 @@ smile_status smile_combine_backward(smile_ctx *ctx, const void *dy, const void *
                                     const int32_t *local_idx, const int32_t *slot, const float *gate,
                                     void *dye, float *dgate, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(dy) || bad(ye) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(gate) || bad(dye) ||
         bad(dgate))
         return SMILE_INVALID_ARG;
@@ -397,6 +450,7 @@ smile_status smile_route_backward(smile_ctx *ctx, const float *logits_inter, con
                                   const int32_t *group_count, const int32_t *local_count, float dloss,
                                   float *dlp, float *dlq, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(logits_inter) || bad(logits_intra) || bad_opt(bias_inter) || bad_opt(bias_intra) ||
         bad(group_idx) || bad(local_idx) || bad(dgate) || bad(group_count) || bad(local_count) || bad(dlp) || bad(dlq))
         return SMILE_INVALID_ARG;
@@ -412,6 +466,7 @@ smile_status smile_expert_ffn_backward(smile_ctx *ctx, const void *xe, const int
                                        void *dxe, void *dw1, void *dw2,
                                        void *workspace, size_t workspace_bytes, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(xe) || bad(kept_count) || bad(w1) || bad(w2) || bad(dye) || bad(dxe) || bad(dw1) || bad(dw2) ||
         bad_opt(h) || bad_opt(pre) || (h == nullptr) != (pre == nullptr))
         return SMILE_INVALID_ARG;
@@ -426,6 +481,7 @@ smile_status smile_dispatch_backward(smile_ctx *ctx, const void *dxe, const int3
                                      const float *dlq, const void *w_inter, const void *w_intra, void *dx,
                                      void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(dxe) || bad(group_idx) || bad(local_idx) || bad(slot) || bad(dlp) || bad(dlq) || bad(w_inter) ||
         bad(w_intra) || bad(dx))
         return SMILE_INVALID_ARG;
@@ -437,6 +493,7 @@ smile_status smile_gate_weights_backward(smile_ctx *ctx, const void *x, const fl
                                          float *dw_inter, float *dw_intra,
                                          void *workspace, size_t workspace_bytes, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || bad(x) || bad(dlp) || bad(dlq) || bad(dw_inter) || bad(dw_intra)) return SMILE_INVALID_ARG;
     const smile_status st = check_backward_workspace(ctx, workspace, workspace_bytes);
     if (st != SMILE_OK) return st;
@@ -447,6 +504,7 @@ smile_status smile_gate_weights_backward(smile_ctx *ctx, const void *x, const fl
 smile_status smile_layer_backward(smile_ctx *ctx, const smile_backward_io *io, float dloss,
                                   void *workspace, size_t workspace_bytes, void *stream)
 {
+    TimerScope timing(ctx);
     if (!ctx || !io) return SMILE_INVALID_ARG;
     if (bad(io->x) || bad(io->w_inter) || bad(io->w_intra) || bad(io->w1) || bad(io->w2) || bad_opt(io->bias_inter) ||
         bad_opt(io->bias_intra) || bad(io->logits_inter) || bad(io->logits_intra) || bad(io->group_idx) ||

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -221,6 +222,31 @@ struct LiveTileWalk {
     __device__ __forceinline__ void advance() { local += local_step; }
 };
 
+// Kernel timing (smile_kernel_timing): while a library call runs on a ctx with events attached, every kernel it
+// launches takes the next caller-owned event pair, which receives the begin / end timestamps of that kernel
+// itself (no launch gaps).  The entry points install the ctx's timer for the duration of the call on the calling
+// thread; launch sites go through SMILE_LAUNCH.
+constexpr int kMaxTimedKernels = 32;
+struct KernelTimer {
+    hipEvent_t *events = nullptr;   // 2 * pairs handles: start, stop, start, stop, ...
+    int pairs = 0, used = 0;
+    const char *names[kMaxTimedKernels] = {};
+};
+extern thread_local KernelTimer *tls_kernel_timer;
+
+template <typename Kernel, typename... Args>
+inline void launch_kernel(const char *name, Kernel kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args)
+{
+    KernelTimer *t = tls_kernel_timer;
+    if (t && t->used < t->pairs) {
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, s, t->events[2 * t->used], t->events[2 * t->used + 1], 0, args...);
+        t->names[t->used++] = name;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+    }
+}
+#define SMILE_LAUNCH(kernel, ...) ::smile::launch_kernel(#kernel, kernel, __VA_ARGS__)
+
 // Tuning overrides and the device's size, fixed when a ctx is created (smile_create reads the SMILE_* environment
 // variables once and asks the runtime for the compute-unit count); -1 = the library's own choice.
 struct Tuning {
@@ -265,6 +291,7 @@ struct smile_ctx {
     void *base;
     size_t bytes;
     bool owns;
+    smile::KernelTimer timer;
 };
 
 namespace smile {
