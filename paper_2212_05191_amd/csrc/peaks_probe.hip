@@ -8,6 +8,8 @@
 //                 streams tiles of 192 rows x K bf16, slab after slab (128 bytes of every row at a K*2-byte
 //                 stride), `depth - 1` slabs in flight; the same bytes laid out contiguously per slab for
 //                 comparison
+//   weight-frags  the same bytes streamed straight into registers by independent waves (no LDS, no barrier), in the
+//                 MFMA operand layout (a lane's 16 bytes of its own row) and in the coalesced layout
 //   l2            L2-resident data (a window of a few MB per XCD) read by register loads and by direct-to-LDS loads
 //   lds           ds_read_b128 issue rate (bytes per second out of LDS, chip-wide)
 //   mfma          back-to-back v_mfma_f32_32x32x16_bf16 with no memory traffic, 1 and 2 waves per SIMD
@@ -94,6 +96,46 @@ __global__ __launch_bounds__(256) void weight_tile_kernel(const u32x4 *w, int K,
         }
     }
     out[blockIdx.x * 256 + tid] = lds[0][tid][0];
+}
+
+// Weight rows streamed straight into registers, no LDS: every wave owns 64 rows of K bf16 (rows K*2 bytes apart)
+// and keeps DEPTH 64-deep slabs (8 loads of 16 bytes per lane each) in flight.
+//   MODE 0: MFMA operand layout -- lane (r = lane % 32, h = lane / 32) loads 16 bytes of row r (or 32 + r) at
+//           k-offset 16*kk + 8*h: an instruction touches 32 rows x 32 bytes
+//   MODE 1: coalesced layout -- 8 consecutive lanes cover 128 bytes of one row: an instruction touches 8 rows
+template <int MODE, int DEPTH>
+__global__ __launch_bounds__(256) void weight_frag_kernel(const u32x4 *w, int K, int tiles, uint32_t *out)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slabs = K / 64, row16 = K / 8;   // 16-byte units per row
+    u32x4 acc = {0, 0, 0, 0};
+    for (int t = blockIdx.x * 4 + wave; t < tiles; t += gridDim.x * 4) {
+        const u32x4 *base = w + (size_t)t * 64 * row16;
+        auto addr = [&](int s, int i) {   // i-th load of slab s
+            if (MODE == 0) return base + (size_t)((i >> 2) * 32 + (lane & 31)) * row16 + s * 8 + (i & 3) * 2 + (lane >> 5);
+            return base + (size_t)(i * 8 + (lane >> 3)) * row16 + s * 8 + (lane & 7);
+        };
+        u32x4 buf[DEPTH][8];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) buf[d][i] = *addr(d < slabs ? d : slabs - 1, i);
+        for (int s = 0; s < slabs; s += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc ^= buf[d][i];
+                const int nx = s + d + DEPTH < slabs ? s + d + DEPTH : slabs - 1;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) buf[d][i] = *addr(nx, i);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc ^= buf[d][i];
+    }
+    out[blockIdx.x * 256 + tid] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
 }
 
 // ------------------------------------------------------------------------------------------ L2 -> CU
@@ -202,6 +244,16 @@ static bool wanted(int argc, char **argv, const char *name)
 }
 
 template <int MODE, int DEPTH>
+static void run_weight_frags(const char *name, const u32x4 *w, int K, int tiles, int per_cu, uint32_t *out)
+{
+    const dim3 grid(g_cus * per_cu);
+    const double us = time_us([&] { hipLaunchKernelGGL((weight_frag_kernel<MODE, DEPTH>), grid, dim3(256), 0, 0, w, K, tiles, out); });
+    const double bytes = (double)tiles * 64 * K * 2;   // the repeats of a tile's last slabs are cache hits
+    printf("weight-frags  %-30s slabs in flight %d  workgroups/CU %d : %8.1f us  %6.2f TB/s\n", name, DEPTH, per_cu, us,
+           bytes / us / 1e6);
+}
+
+template <int MODE, int DEPTH>
 static void run_weight_tiles(const char *name, const u32x4 *w, int K, int tiles, int per_cu, uint32_t *out)
 {
     const dim3 grid(g_cus * per_cu);
@@ -257,6 +309,22 @@ int main(int argc, char **argv)
         run_weight_tiles<0, 4>("rows 2 KB apart (as stored)", w, K, tiles, 1, out);
         run_weight_tiles<0, 6>("rows 2 KB apart (as stored)", w, K, tiles, 1, out);
         run_weight_tiles<1, 6>("slab-contiguous", w, K, tiles, 1, out);
+        CK(hipFree(w));
+    }
+
+    if (wanted(argc, argv, "weight-frags")) {
+        const int K = 1024, tiles = 16896;   // 16896 wave tiles x 128 KB = 2.2 GB
+        u32x4 *w;
+        const size_t bytes = (size_t)tiles * 64 * K * 2;
+        CK(hipMalloc(&w, bytes));
+        CK(hipMemset(w, 1, bytes));
+        run_weight_frags<0, 2>("MFMA layout, 32 rows x 32 B", w, K, tiles, 2, out);
+        run_weight_frags<0, 3>("MFMA layout, 32 rows x 32 B", w, K, tiles, 2, out);
+        run_weight_frags<0, 4>("MFMA layout, 32 rows x 32 B", w, K, tiles, 2, out);
+        run_weight_frags<1, 2>("coalesced, 8 rows x 128 B", w, K, tiles, 2, out);
+        run_weight_frags<1, 3>("coalesced, 8 rows x 128 B", w, K, tiles, 2, out);
+        run_weight_frags<1, 4>("coalesced, 8 rows x 128 B", w, K, tiles, 2, out);
+        run_weight_frags<1, 3>("coalesced, 8 rows x 128 B", w, K, tiles, 1, out);
         CK(hipFree(w));
     }
 
