@@ -41,6 +41,13 @@ def build(verbose: bool = False, jobs: int | None = None, only: list[str] | None
     os.makedirs(OBJ, exist_ok=True)
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
+    if only is not None:
+        # an object older than any header is stale whatever the caller asked for (struct layouts are shared)
+        headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".h"))]
+        headers += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+        newest = max(os.path.getmtime(h) for h in headers)
+        only = list(only) + [s for s, o in zip(SOURCES, objs)
+                             if s not in only and (not os.path.exists(o) or os.path.getmtime(o) < newest)]
     cmds = [[hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)
             if only is None or s in only]
     # the stand-alone microbenchmark of the chip's measured peak rates (no library code in it)
