@@ -236,3 +236,26 @@ def test_static_scratch_routing_rejects_before_any_launch():
     huge = _desc(T=1 << 22, n_groups=32, m_local=8, capacity=20000)
     assert lib.smile_validate_desc(C.byref(huge)) == B.OK
     assert lib.smile_route_bilevel_static(C.byref(huge), *args, None) == B.WORKSPACE
+
+
+def test_kernel_timing_argument_checks():
+    """smile_kernel_timing stores caller-owned event handles in the ctx; its checks need no GPU."""
+    lib = B.load()
+    d = _desc()
+    h = C.c_void_p(None)
+    fake = 0x7F0000000000
+    assert lib.smile_create_with_workspace(C.byref(d), fake, B.smile_workspace_bytes(d), C.byref(h)) == B.OK
+    try:
+        ev = (C.c_void_p * 8)(*[fake + 64 * (i + 1) for i in range(8)])
+        assert lib.smile_kernel_timing(None, ev, 4) == B.INVALID_ARG
+        assert lib.smile_kernel_timing(h, None, 4) == B.INVALID_ARG
+        assert lib.smile_kernel_timing(h, ev, -1) == B.INVALID_ARG
+        holes = (C.c_void_p * 8)(*[fake + 64 * (i + 1) if i != 5 else None for i in range(8)])
+        assert lib.smile_kernel_timing(h, holes, 4) == B.INVALID_ARG       # a NULL handle among the 2 * pairs
+        assert lib.smile_kernel_timing(h, ev, 4) == B.OK
+        assert lib.smile_kernel_timing_count(h) == 0                        # no call has run yet
+        assert lib.smile_kernel_timing_name(h, 0) == b"" and lib.smile_kernel_timing_name(h, -1) == b""
+        assert lib.smile_kernel_timing(h, None, 0) == B.OK                  # detach
+        assert lib.smile_kernel_timing_count(None) == 0
+    finally:
+        assert lib.smile_destroy(h) == B.OK

@@ -261,6 +261,51 @@ def test_work_runs_on_the_callers_stream(torch_cuda):
         b.close()
 
 
+def test_kernel_timing_leaves_results_unchanged(torch_cuda):
+    """smile_kernel_timing: every kernel of a call takes a caller-owned event pair; the outputs keep their bits,
+    the reported kernels are the call's launches in order, and each pair yields a positive duration."""
+    import ctypes
+    torch = torch_cuda
+    cfg = wl.small_config("timing", 5000, 128, 256, 3, 4, 450, "bf16", "gelu", skew=True, seed=39)
+    layer = _run(cfg, "fused")
+    try:
+        lib = B.load()
+        hip = ctypes.CDLL("libamdhip64.so")
+        hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        first = parity.fetch(layer)
+        evs = []
+        for _ in range(16):
+            e = ctypes.c_void_p()
+            assert hip.hipEventCreate(ctypes.byref(e)) == 0
+            evs.append(e)
+        arr = (ctypes.c_void_p * 16)(*[e.value for e in evs])
+        assert lib.smile_kernel_timing(layer.ctx.handle, arr, 8) == 0
+        layer.forward_fused()
+        n = lib.smile_kernel_timing_count(layer.ctx.handle)
+        names = [lib.smile_kernel_timing_name(layer.ctx.handle, i).decode() for i in range(n)]
+        torch.cuda.synchronize()
+        _say(f"   kernels: {names}")
+        assert 4 <= n <= 6 and "gate_logits" in names[0] and sum("grouped_gemm" in k for k in names) == 2
+        for i in range(n):
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), evs[2 * i], evs[2 * i + 1]) == 0
+            assert 0.0 < ms.value < 50.0, (names[i], ms.value)
+        again = parity.fetch(layer)
+        for k in first:
+            if k not in ("xe", "ye"):
+                np.testing.assert_array_equal(first[k], again[k], err_msg=k)
+        # detached: the next call takes no events and gives the same bits
+        assert lib.smile_kernel_timing(layer.ctx.handle, None, 0) == 0
+        layer.forward_fused()
+        assert lib.smile_kernel_timing_count(layer.ctx.handle) == 0
+        third = parity.fetch(layer)
+        np.testing.assert_array_equal(first["y"], third["y"])
+        for e in evs:
+            hip.hipEventDestroy(e)
+    finally:
+        layer.close()
+
+
 def test_expert_biases(torch_cuda):
     """Optional b1 / b2 of the expert FFN (NULL in the benchmark configurations)."""
     torch = torch_cuda
