@@ -34,6 +34,16 @@ def _run(cmd, verbose):
         print(out)
 
 
+def sources_to_compile(only, sources, objs, headers):
+    """The sources an incremental build compiles: those asked for, plus every source whose object is missing or
+    older than the newest header (struct layouts are shared between the objects, so such an object is stale
+    whatever the caller asked for).  Names in `only` that are not library sources (the probe) pass through."""
+    newest = max((os.path.getmtime(h) for h in headers), default=0.0)
+    stale = [s for s, o in zip(sources, objs)
+             if s not in only and (not os.path.exists(o) or os.path.getmtime(o) < newest)]
+    return list(only) + stale
+
+
 def build(verbose: bool = False, jobs: int | None = None, only: list[str] | None = None) -> str:
     """Compile every source (always: no staleness check) and link the library and the peak-rate probe.
     only: recompile just these sources (the other objects must exist from an earlier full build) and relink."""
@@ -42,12 +52,9 @@ def build(verbose: bool = False, jobs: int | None = None, only: list[str] | None
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
     if only is not None:
-        # an object older than any header is stale whatever the caller asked for (struct layouts are shared)
         headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".h"))]
         headers += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
-        newest = max(os.path.getmtime(h) for h in headers)
-        only = list(only) + [s for s, o in zip(SOURCES, objs)
-                             if s not in only and (not os.path.exists(o) or os.path.getmtime(o) < newest)]
+        only = sources_to_compile(only, SOURCES, objs, headers)
     cmds = [[hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)
             if only is None or s in only]
     # the stand-alone microbenchmark of the chip's measured peak rates (no library code in it)
