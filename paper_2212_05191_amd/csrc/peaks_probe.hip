@@ -4,6 +4,7 @@
 //
 //   copy          plain device copy, 1 GiB read + 1 GiB written (16 bytes per lane)
 //   read          read-only stream of 2 GiB (register loads, 16 bytes per lane, 8 loads in flight per lane)
+//   fill          store-only stream of 2 GiB (16 bytes per lane, no reads)
 //   weight-tiles  the expert GEMM's weight access pattern, read-only, through direct-to-LDS loads: a workgroup
 //                 streams tiles of 192 rows x K bf16, slab after slab (128 bytes of every row at a K*2-byte
 //                 stride), `depth - 1` slabs in flight; the same bytes laid out contiguously per slab for
@@ -44,6 +45,14 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src
 {
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// stores only: the ceiling of a kernel whose traffic is its output (the weight-gradient GEMMs of small experts)
+__global__ __launch_bounds__(256) void fill_kernel(u32x4 *__restrict__ dst, size_t n16, uint32_t value)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    const u32x4 v = {value, value, value, value};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = v;
 }
 
 __global__ __launch_bounds__(256) void read_kernel(const u32x4 *__restrict__ src, size_t n16, uint32_t *out)
@@ -275,7 +284,7 @@ int main(int argc, char **argv)
     uint32_t *out;
     CK(hipMalloc(&out, (size_t)g_cus * 8 * 256 * 4));
 
-    if (wanted(argc, argv, "copy") || wanted(argc, argv, "read")) {
+    if (wanted(argc, argv, "copy") || wanted(argc, argv, "read") || wanted(argc, argv, "fill")) {
         const size_t bytes = (size_t)1 << 30;
         u32x4 *a, *b;
         CK(hipMalloc(&a, 2 * bytes));
@@ -291,6 +300,12 @@ int main(int argc, char **argv)
             for (int per_cu : {4, 8, 16}) {
                 const double us = time_us([&] { hipLaunchKernelGGL(read_kernel, dim3(g_cus * per_cu), dim3(256), 0, 0, a, 2 * bytes / 16, out); });
                 printf("read          2 GiB, register loads            workgroups/CU %2d : %8.1f us  %6.2f TB/s\n", per_cu, us,
+                       2.0 * bytes / us / 1e6);
+            }
+        if (wanted(argc, argv, "fill"))
+            for (int per_cu : {4, 8, 16}) {
+                const double us = time_us([&] { hipLaunchKernelGGL(fill_kernel, dim3(g_cus * per_cu), dim3(256), 0, 0, a, 2 * bytes / 16, 7u); });
+                printf("fill          2 GiB written, no reads          workgroups/CU %2d : %8.1f us  %6.2f TB/s\n", per_cu, us,
                        2.0 * bytes / us / 1e6);
             }
         CK(hipFree(a));
